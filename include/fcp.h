@@ -1,0 +1,162 @@
+/*
+ * libfcp -- rank-local attention of Flexible Context Parallelism on MI355X (gfx950).
+ *
+ * The paper assigns every packed sequence to a context-parallel (CP) group whose degree
+ * may be ANY positive integer (Sec. 4.2) and computes attention (Eq. 1, Sec. 3.1; causal
+ * for language models, Sec. 4.3) ring-style: each rank keeps its share of the queries
+ * while key/value blocks travel round the group (Sec. 3.2, Sec. 4.3 communication cost).
+ * This library is the work ONE rank does: a shard plan, one partial attention result per
+ * ring step, the log-sum-exp merge of those partials, and the matching backward.
+ *
+ * Conventions
+ *   - plain C ABI, no exceptions; every call returns 0 (FCP_OK) or a negative FCP_ERR_*;
+ *     fcp_last_error() returns a thread-local message for the last failing call.
+ *   - the CALLER owns all memory, host and device.  The library allocates no device memory;
+ *     kernels that need a work area take `scratch` sized by fcp_scratch_bytes().
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers are
+ *     ordinary host memory.  Device calls enqueue work on `stream` (a hipStream_t passed as
+ *     void*, NULL = default stream) and return without synchronising.  Outputs are
+ *     undefined after an error return.
+ *   - bf16 tensors are raw 16-bit patterns; fp32 is IEEE binary32.
+ *   - layouts (row-major, last index fastest):
+ *       Q, dO, O, dQ      [tq , hq , head_dim]   rows = the rank's local (packed) query rows
+ *       K, V, dK, dV      [tkv, hkv, head_dim]   the resident pool: every sequence unsharded,
+ *                                                in input order; sequence n starts at row
+ *                                                cu_seqlens_kv[n]
+ *       LSE, Delta        [hq, tq]  fp32 (head-major)
+ *       partial O         [n_parts][tq, hq, head_dim]  fp32
+ *       partial LSE       [n_parts][hq, tq]            fp32
+ *   - query head h reads KV head h / (hq / hkv); hq % hkv == 0; head_dim is 64 or 128.
+ *   - LSE is the natural log of the sum of exp of the SCALED scores; -inf marks "no key".
+ */
+#ifndef FCP_H_
+#define FCP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FCP_OK 0
+#define FCP_ERR_INVALID_ARG (-1)
+#define FCP_ERR_CAPACITY (-2)
+#define FCP_ERR_UNSUPPORTED (-3)
+#define FCP_ERR_HIP (-4)
+
+/* One per (sequence, zigzag chunk), sorted by (rank, seq, chunk).  24 bytes. */
+typedef struct fcp_chunk_desc {
+  int32_t seq;        /* index into seq_lens                                             */
+  int32_t rank;       /* base_rank[seq] + group-local rank                               */
+  int32_t chunk;      /* 0 .. 2d-1 (0 only when the degree d is 1)                       */
+  int32_t seq_start;  /* first token position of the chunk inside its sequence          */
+  int32_t len;        /* tokens in the chunk (0 is possible when L < 2d)                 */
+  int32_t local_off;  /* row offset of the chunk in that rank's packed Q/O/dO/dQ buffers */
+} fcp_chunk_desc;
+
+/* One per (rank, ring step, sequence, query chunk) that sees at least one key.  44 bytes.
+ * The mask is implied by positions: a key is visible iff k_pos <= q_pos, where
+ * q_pos = q_seq_start + row and k_pos = k_seq_start[s] + key inside segment s.
+ * Sorted by (rank, step, seq, q_seq_start).  Unused segment fields are 0. */
+typedef struct fcp_work_desc {
+  int32_t seq, rank, step;      /* step s reads the KV chunks of group-local rank (i - s) mod d;
+                                   it is also the partial slot this item writes            */
+  int32_t q_local_off, q_seq_start, q_len;
+  int32_t n_seg;                /* 1 or 2 key/value segments, increasing positions         */
+  int32_t k_seq_start[2], k_len[2];
+} fcp_work_desc;
+
+/* Message of the last error on the calling thread ("" if none).  Never NULL. */
+const char* fcp_last_error(void);
+
+/*
+ * fcp_shard_plan -- HOST ONLY, integer exact.
+ * Splits every sequence for its CP degree (the paper: an even split over the d ranks of
+ * the group, Sec. 4.3; any integer d, Sec. 4.2) in the load-balanced zigzag form:
+ * degree 1 -> one chunk; degree d > 1 -> 2d chunks, the first (L mod 2d) one token longer,
+ * group-local rank i owning chunks i and 2d-1-i.  Emits the chunk table and, per
+ * (rank, ring step), the work items (query chunk x visible KV segments).
+ *   seq_lens, cp_degree [n_seqs] host, lengths >= 1, degrees >= 1
+ *   base_rank [n_seqs] host or NULL (all 0): first global rank of each sequence's group
+ *   chunks / work: host output arrays of chunk_cap / work_cap entries, or NULL to only count
+ *   n_chunks / n_work: host, always written with the required counts
+ * Returns FCP_ERR_CAPACITY if a non-NULL array is too small (counts are still written).
+ */
+int fcp_shard_plan(const int32_t* seq_lens, const int32_t* cp_degree, const int32_t* base_rank,
+                   int32_t n_seqs, fcp_chunk_desc* chunks, int64_t chunk_cap, int64_t* n_chunks,
+                   fcp_work_desc* work, int64_t work_cap, int64_t* n_work);
+
+/* Scratch size in bytes for `which` = FCP_SCRATCH_FWD or FCP_SCRATCH_BWD. */
+#define FCP_SCRATCH_FWD 0
+#define FCP_SCRATCH_BWD 1
+size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t hq, int32_t hkv,
+                         int32_t head_dim, int64_t n_work, int32_t n_parts);
+
+/*
+ * fcp_attn_fwd_step -- partial attention of one rank for one or several ring steps.
+ * For every work item, every row of its query chunk and every head: softmax(scale q.K^T)
+ * V over the item's VISIBLE keys only (Eq. 1 restricted to the keys present in that ring
+ * step), normalised by that step's own sum, written to partial slot `step` together with
+ * LSE_step.  Rows that no item of a slot covers get LSE = -inf in that slot and their
+ * partial O rows are left unwritten (fcp_lse_merge never reads them).
+ *   q [tq,hq,D], k, v [tkv,hkv,D]           bf16 device
+ *   cu_seqlens_kv [n_seqs+1]                 int32 device
+ *   work [n_work]                            device; this rank's items, any subset of steps
+ *   n_parts                                  number of partial slots; every item needs step < n_parts
+ *   o_part [n_parts][tq,hq,D] fp32, lse_part [n_parts][hq,tq] fp32       device outputs
+ *   scratch                                  device, >= fcp_scratch_bytes(FCP_SCRATCH_FWD, ...), 256-byte aligned
+ * Items are checked on the device against tq, tkv, n_seqs and n_parts; an item that fails is
+ * skipped and counted (see fcp_scratch_status); no access leaves the given extents.
+ * Two items that cover the same (row, step) are a caller error (last writer wins).
+ */
+int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                      int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                      int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                      float softmax_scale, float* o_part, float* lse_part,
+                      void* scratch, size_t scratch_bytes, void* stream);
+
+/*
+ * fcp_lse_merge -- combine the partials of the ring steps (online-softmax rescaling):
+ *   LSE = ln sum_s exp(LSE_s),   O = sum_s exp(LSE_s - LSE) O_s.
+ * A slot with LSE_s = -inf contributes nothing and its O rows are not read; a row whose
+ * slots are all -inf gets O = 0, LSE = -inf.  o [tq,hq,D] bf16 (round to nearest even),
+ * lse [hq,tq] fp32.  All pointers device.
+ */
+int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
+                  int32_t hq, int32_t head_dim, void* o, float* lse, void* stream);
+
+/* Backward prologue: delta[h, i] = sum_c dO[i,h,c] * O[i,h,c]  (fp32).  Device pointers. */
+int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, int32_t head_dim,
+                       float* delta, void* stream);
+
+/*
+ * fcp_attn_bwd_step -- gradient contributions of one rank for one or several ring steps.
+ * With P = exp(scale q.K^T - LSE) on the visible pairs of each work item (LSE = merged),
+ *   dV += P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ += scale dS K,  dK += scale dS^T Q,
+ * dK/dV summed over the hq/hkv query heads of a KV head.  The three fp32 accumulators are
+ * ADDED to (caller zeroes them before the first step): dq_acc [tq,hq,D], dk_acc, dv_acc
+ * [tkv,hkv,D].  Accumulation uses fp32 atomics, so the summation order varies run to run.
+ * Other arguments as in fcp_attn_fwd_step; scratch sized with FCP_SCRATCH_BWD.
+ */
+int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d_o,
+                      const float* lse, const float* delta, const int32_t* cu_seqlens_kv,
+                      int32_t n_seqs, const fcp_work_desc* work, int64_t n_work,
+                      int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                      float softmax_scale, float* dq_acc, float* dk_acc, float* dv_acc,
+                      void* scratch, size_t scratch_bytes, void* stream);
+
+/* Cast n fp32 accumulator values to bf16, round to nearest even.  Device pointers. */
+int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, void* stream);
+
+/*
+ * Reads back what the last fwd/bwd step that used `scratch` recorded: the number of
+ * scheduled tiles and the number of rejected work items.  Synchronises `stream`.
+ * Either output pointer (host) may be NULL.
+ */
+int fcp_scratch_status(const void* scratch, void* stream, int32_t* n_tiles, int32_t* n_rejected);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FCP_H_ */

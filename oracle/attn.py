@@ -35,7 +35,7 @@ def _load():
         lib.oracle_attn_fwd.restype = None
         lib.oracle_attn_dq.argtypes = [P, P, P, P, P, I, I, I, I, D, P, L, P, P, P]
         lib.oracle_attn_dq.restype = None
-        lib.oracle_attn_dkv.argtypes = [P, P, P, P, P, I, L, I, I, I, D, P, L, P, P, P, P]
+        lib.oracle_attn_dkv.argtypes = [P, P, P, P, P, I, L, I, I, I, D, P, L, P, P, P, L, P, P]
         lib.oracle_attn_dkv.restype = None
         lib.oracle_num_threads.restype = I
         _lib = lib
@@ -71,25 +71,49 @@ def attn_fwd(q, k, v, cu_seqlens, scale, rows=None):
     return O, LSE
 
 
-def attn_bwd(q, k, v, d_o, cu_seqlens, scale, rows=None, O=None, LSE=None, want_dkv=True):
-    """Gradients of sum(O*dO).  Returns dQ [n_rows,Hq,D], dK, dV [T,Hkv,D] (fp64); dK/dV are
-    summed over the listed query rows only."""
+def attn_dq(q, k, v, d_o, cu_seqlens, scale, rows, O, LSE):
+    """dQ [n_rows,Hq,D] for the listed rows; O, LSE are the oracle's forward results for them."""
     q, k, v, d_o = (_chk(x, np.uint16) for x in (q, k, v, d_o))
     cu = _chk(cu_seqlens, np.int32)
     T, hq, D = q.shape
     hkv = k.shape[1]
+    rows = _chk(rows, np.int64)
+    O, LSE = _chk(O, np.float64), _chk(LSE, np.float64)
+    assert O.shape == (len(rows), hq, D) and LSE.shape == (len(rows), hq)
+    dQ = np.empty((len(rows), hq, D), np.float64)
+    _load().oracle_attn_dq(_p(q), _p(k), _p(v), _p(d_o), _p(cu), len(cu) - 1, hq, hkv, D, float(scale),
+                           _p(rows), len(rows), _p(O), _p(LSE), _p(dQ))
+    return dQ
+
+
+def attn_dkv(q, k, v, d_o, cu_seqlens, scale, rows, O, LSE, keys=None):
+    """dK, dV summed over the listed query rows, for the listed keys (all T tokens if None)."""
+    q, k, v, d_o = (_chk(x, np.uint16) for x in (q, k, v, d_o))
+    cu = _chk(cu_seqlens, np.int32)
+    T, hq, D = q.shape
+    hkv = k.shape[1]
+    rows = _chk(rows, np.int64)
+    O, LSE = _chk(O, np.float64), _chk(LSE, np.float64)
+    assert O.shape == (len(rows), hq, D) and LSE.shape == (len(rows), hq)
+    nk = T if keys is None else len(keys)
+    keys_a = None if keys is None else _chk(keys, np.int64)
+    dK = np.empty((nk, hkv, D), np.float64)
+    dV = np.empty((nk, hkv, D), np.float64)
+    _load().oracle_attn_dkv(_p(q), _p(k), _p(v), _p(d_o), _p(cu), len(cu) - 1, T, hq, hkv, D, float(scale),
+                            _p(rows), len(rows), _p(O), _p(LSE), None if keys_a is None else _p(keys_a), nk,
+                            _p(dK), _p(dV))
+    return dK, dV
+
+
+def attn_bwd(q, k, v, d_o, cu_seqlens, scale, rows=None, O=None, LSE=None, want_dkv=True):
+    """Gradients of sum(O*dO).  Returns dQ [n_rows,Hq,D], dK, dV [T,Hkv,D] (fp64); dK/dV are
+    summed over the listed query rows only."""
+    T = np.asarray(q).shape[0]
     rows = np.arange(T, dtype=np.int64) if rows is None else _chk(rows, np.int64)
     if O is None or LSE is None:
-        O, LSE = attn_fwd(q, k, v, cu, scale, rows)
-    O, LSE = _chk(O, np.float64), _chk(LSE, np.float64)
-    dQ = np.empty((len(rows), hq, D), np.float64)
-    lib = _load()
-    lib.oracle_attn_dq(_p(q), _p(k), _p(v), _p(d_o), _p(cu), len(cu) - 1, hq, hkv, D, float(scale),
-                       _p(rows), len(rows), _p(O), _p(LSE), _p(dQ))
+        O, LSE = attn_fwd(q, k, v, cu_seqlens, scale, rows)
+    dQ = attn_dq(q, k, v, d_o, cu_seqlens, scale, rows, O, LSE)
     if not want_dkv:
         return dQ, None, None
-    dK = np.empty((T, hkv, D), np.float64)
-    dV = np.empty((T, hkv, D), np.float64)
-    lib.oracle_attn_dkv(_p(q), _p(k), _p(v), _p(d_o), _p(cu), len(cu) - 1, T, hq, hkv, D, float(scale),
-                        _p(rows), len(rows), _p(O), _p(LSE), _p(dK), _p(dV))
+    dK, dV = attn_dkv(q, k, v, d_o, cu_seqlens, scale, rows, O, LSE)
     return dQ, dK, dV

@@ -132,12 +132,14 @@ void oracle_attn_dq(const uint16_t* q, const uint16_t* k, const uint16_t* v, con
   }
 }
 
-/* dK, dV [T, Hkv, D]: sums over the listed query rows only.  Parallel over keys, so
- * every output element has a single writer. */
+/* dK, dV [n_keys, Hkv, D] for the listed keys (global token ids; keys == NULL means all T
+ * tokens in order): sums over the listed query rows only.  Parallel over keys, so every
+ * output element has a single writer. */
 void oracle_attn_dkv(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* d_o,
                      const int32_t* cu_seqlens, int n_seqs, int64_t T, int hq, int hkv, int D,
                      double scale, const int64_t* rows, int64_t n_rows,
-                     const double* O, const double* LSE, double* dK, double* dV) {
+                     const double* O, const double* LSE, const int64_t* keys, int64_t n_keys,
+                     double* dK, double* dV) {
   const int G = hq / hkv;
   /* Delta per (row, head) once */
   double* delta = (double*)malloc(sizeof(double) * (size_t)n_rows * hq);
@@ -149,13 +151,15 @@ void oracle_attn_dkv(const uint16_t* q, const uint16_t* k, const uint16_t* v, co
       for (int c = 0; c < D; ++c) d += bf(doi[c]) * oi[c];
       delta[r * hq + h] = d;
     }
+  if (keys == NULL) n_keys = T;
 #pragma omp parallel for schedule(dynamic, 16)
-  for (int64_t tj = 0; tj < T; ++tj) {
+  for (int64_t kidx = 0; kidx < n_keys; ++kidx) {
+    const int64_t tj = keys ? keys[kidx] : kidx;
     const int n = seq_of(cu_seqlens, n_seqs, tj);
     const int64_t t1 = cu_seqlens[n + 1];
     for (int g = 0; g < hkv; ++g) {
-      double* dk = dK + (tj * hkv + g) * (int64_t)D;
-      double* dv = dV + (tj * hkv + g) * (int64_t)D;
+      double* dk = dK + (kidx * hkv + g) * (int64_t)D;
+      double* dv = dV + (kidx * hkv + g) * (int64_t)D;
       for (int c = 0; c < D; ++c) { dk[c] = 0.0; dv[c] = 0.0; }
     }
     for (int64_t r = 0; r < n_rows; ++r) {
@@ -165,8 +169,8 @@ void oracle_attn_dkv(const uint16_t* q, const uint16_t* k, const uint16_t* v, co
         const int g = h / G;
         const uint16_t* kj = k + (tj * hkv + g) * (int64_t)D;
         const uint16_t* vj = v + (tj * hkv + g) * (int64_t)D;
-        double* dk = dK + (tj * hkv + g) * (int64_t)D;
-        double* dv = dV + (tj * hkv + g) * (int64_t)D;
+        double* dk = dK + (kidx * hkv + g) * (int64_t)D;
+        double* dv = dV + (kidx * hkv + g) * (int64_t)D;
         const uint16_t* qi = q + (ti * hq + h) * (int64_t)D;
         const uint16_t* doi = d_o + (ti * hq + h) * (int64_t)D;
         const double p = exp(scale * dot_bf(qi, kj, D) - LSE[r * hq + h]);

@@ -1,0 +1,162 @@
+"""Thin ctypes binding of libfcp.so: the same entry points as include/fcp.h, argument
+marshalling only.  Device buffers are torch tensors (PyTorch is used for device memory and
+streams, nothing else); every step of the path runs in the library's own kernels.
+
+There is no fallback: if libfcp.so is missing or does not load, importing a function from
+here raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfcp.so")
+
+FCP_OK, FCP_ERR_INVALID_ARG, FCP_ERR_CAPACITY, FCP_ERR_UNSUPPORTED, FCP_ERR_HIP = 0, -1, -2, -3, -4
+FCP_SCRATCH_FWD, FCP_SCRATCH_BWD = 0, 1
+
+CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("rank", "<i4"), ("chunk", "<i4"),
+                        ("seq_start", "<i4"), ("len", "<i4"), ("local_off", "<i4")])
+WORK_DTYPE = np.dtype([("seq", "<i4"), ("rank", "<i4"), ("step", "<i4"),
+                       ("q_local_off", "<i4"), ("q_seq_start", "<i4"), ("q_len", "<i4"),
+                       ("n_seg", "<i4"), ("k_seq_start", "<i4", (2,)), ("k_len", "<i4", (2,))])
+
+EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
+           "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status"]
+
+
+class FcpError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libfcp error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libfcp.so (built in-tree by paper_2602_21788_amd.build); builds it if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        P, I32, I64, F, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+        L.fcp_last_error.restype = ctypes.c_char_p
+        L.fcp_last_error.argtypes = []
+        L.fcp_shard_plan.restype = ctypes.c_int
+        L.fcp_shard_plan.argtypes = [P, P, P, I32, P, I64, P, P, I64, P]
+        L.fcp_scratch_bytes.restype = SZ
+        L.fcp_scratch_bytes.argtypes = [ctypes.c_int, I32, I32, I32, I32, I32, I64, I32]
+        L.fcp_attn_fwd_step.restype = ctypes.c_int
+        L.fcp_attn_fwd_step.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, I32, F, P, P, P, SZ, P]
+        L.fcp_lse_merge.restype = ctypes.c_int
+        L.fcp_lse_merge.argtypes = [P, P, I32, I32, I32, I32, P, P, P]
+        L.fcp_attn_bwd_delta.restype = ctypes.c_int
+        L.fcp_attn_bwd_delta.argtypes = [P, P, I32, I32, I32, P, P]
+        L.fcp_attn_bwd_step.restype = ctypes.c_int
+        L.fcp_attn_bwd_step.argtypes = [P, P, P, P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, F, P, P, P, P, SZ, P]
+        L.fcp_grad_finalize.restype = ctypes.c_int
+        L.fcp_grad_finalize.argtypes = [P, P, I64, P]
+        L.fcp_scratch_status.restype = ctypes.c_int
+        L.fcp_scratch_status.argtypes = [P, P, P, P]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int):
+    if rc != FCP_OK:
+        raise FcpError(rc, lib().fcp_last_error().decode())
+
+
+def _np_ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev_ptr(t):
+    """Device pointer of a torch tensor (must be contiguous and on a GPU)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(int(getattr(stream, "cuda_stream", stream)))
+
+
+# ---------------------------------------------------------------------------------------
+def fcp_shard_plan(seq_lens, cp_degree, base_rank=None):
+    """Host only.  Returns (chunks, work) numpy structured arrays (CHUNK_DTYPE, WORK_DTYPE)."""
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    cd = np.ascontiguousarray(cp_degree, dtype=np.int32)
+    if sl.shape != cd.shape or sl.ndim != 1:
+        raise ValueError("seq_lens and cp_degree must be 1-D and the same length")
+    br = None if base_rank is None else np.ascontiguousarray(base_rank, dtype=np.int32)
+    if br is not None and br.shape != sl.shape:
+        raise ValueError("base_rank must match seq_lens")
+    nc, nw = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().fcp_shard_plan(_np_ptr(sl), _np_ptr(cd), _np_ptr(br), len(sl), None, 0, ctypes.byref(nc),
+                                None, 0, ctypes.byref(nw)))
+    chunks = np.zeros(nc.value, CHUNK_DTYPE)
+    work = np.zeros(nw.value, WORK_DTYPE)
+    _check(lib().fcp_shard_plan(_np_ptr(sl), _np_ptr(cd), _np_ptr(br), len(sl), _np_ptr(chunks), nc.value,
+                                ctypes.byref(nc), _np_ptr(work), nw.value, ctypes.byref(nw)))
+    return chunks, work
+
+
+def fcp_scratch_bytes(which, tq, tkv, hq, hkv, head_dim, n_work, n_parts) -> int:
+    return int(lib().fcp_scratch_bytes(which, tq, tkv, hq, hkv, head_dim, n_work, n_parts))
+
+
+def fcp_attn_fwd_step(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, o_part, lse_part, scratch, stream=None):
+    """q [tq,hq,D], k/v [tkv,hkv,D] bf16; cu_seqlens_kv int32 [n_seqs+1]; work: uint8 device tensor
+    holding fcp_work_desc records; o_part [n_parts,tq,hq,D] fp32; lse_part [n_parts,hq,tq] fp32."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_fwd_step(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(cu_seqlens_kv),
+                                   cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, n_parts, tq, tkv, hq, hkv, D,
+                                   float(softmax_scale), _dev_ptr(o_part), _dev_ptr(lse_part), _dev_ptr(scratch),
+                                   scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_lse_merge(o_part, lse_part, o, lse, stream=None):
+    n_parts, tq, hq, D = o_part.shape
+    _check(lib().fcp_lse_merge(_dev_ptr(o_part), _dev_ptr(lse_part), n_parts, tq, hq, D, _dev_ptr(o), _dev_ptr(lse),
+                               _stream(stream)))
+
+
+def fcp_attn_bwd_delta(o, d_o, delta, stream=None):
+    tq, hq, D = o.shape
+    _check(lib().fcp_attn_bwd_delta(_dev_ptr(o), _dev_ptr(d_o), tq, hq, D, _dev_ptr(delta), _stream(stream)))
+
+
+def fcp_attn_bwd_step(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softmax_scale, dq_acc, dk_acc, dv_acc, scratch,
+                      stream=None):
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_bwd_step(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(d_o), _dev_ptr(lse), _dev_ptr(delta),
+                                   _dev_ptr(cu_seqlens_kv), cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, tq, tkv,
+                                   hq, hkv, D, float(softmax_scale), _dev_ptr(dq_acc), _dev_ptr(dk_acc), _dev_ptr(dv_acc),
+                                   _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_grad_finalize(acc, out_bf16, stream=None):
+    _check(lib().fcp_grad_finalize(_dev_ptr(acc), _dev_ptr(out_bf16), acc.numel(), _stream(stream)))
+
+
+def fcp_scratch_status(scratch, stream=None):
+    """(n_tiles, n_rejected) recorded by the last step that used `scratch`; synchronises."""
+    a, b = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().fcp_scratch_status(_dev_ptr(scratch), _stream(stream), ctypes.byref(a), ctypes.byref(b)))
+    return a.value, b.value

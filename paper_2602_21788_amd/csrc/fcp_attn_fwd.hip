@@ -1,0 +1,368 @@
+// fcp_attn_fwd_step: partial causal attention of one CP rank for its ring steps.
+//
+// Function computed: softmax(scale Q K^T) V (paper Eq. 1, Sec. 3.1) with the causal mask
+// (Sec. 4.3), restricted to the keys one ring step brings (ring-style CP, Sec. 3.2), for
+// packed sequences of heterogeneous length (Sec. 4.1).  Per row the kernel emits the
+// locally normalised output and LSE = ln sum exp(scaled scores).
+//
+// gfx950 design
+//   * persistent 256-thread blocks (4 wave64) pull (query tile, head) units from per-XCD
+//     counters; the tile list is sorted longest-first by the scheduler kernel;
+//   * a unit = 128 query rows of one work item for one query head; wave w owns rows
+//     32w .. 32w+31 and keeps its Q fragments in registers for the whole unit;
+//   * K/V stream through LDS in 64-key tiles, double buffered, global loads for tile t+1 in
+//     flight while tile t is computed; one barrier per tile;
+//   * scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane then
+//     holds 16 keys of ONE query column, so the row maximum and sum are in-lane reductions
+//     plus a single exchange with the lane 32 away, and the exponentiated scores are already
+//     in the B-operand layout of the second contraction O^T += V^T P^T;
+//   * V^T fragments come from the row-major V tile through ds_read_b64_tr_b16 (LDS
+//     transpose read), so V is never transposed in memory;
+//   * key tiles that lie completely below the diagonal skip the mask; key tiles completely
+//     above it are never visited (the loop bound comes from the last row's position).
+#include "fcp_internal.h"
+
+namespace fcp {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct FwdParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const int32_t* cu;
+  const fcp_work_desc* work;
+  const SchedHeader* hdr_ro;
+  SchedHeader* hdr;
+  const Tile* tiles;
+  float* o_part;
+  float* lse_part;
+  int32_t tq, hq, hkv;
+  float scale_log2;  // softmax_scale * log2(e)
+};
+
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ inline float lane32_partner_max(float x) {
+  // v_permlane32_swap exchanges the upper half of the first operand with the lower half of
+  // the second; with both operands = x every lane ends up holding x of lanes l and l^32.
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+  return fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+}
+__device__ inline float lane32_partner_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+  return __int_as_float(r[0]) + __int_as_float(r[1]);
+}
+
+template <int D>
+struct FwdCfg {
+  static constexpr int BM = kFwdBM;               // 128 query rows per unit (32 per wave)
+  static constexpr int BN = kFwdBN;               // 64 keys per LDS tile
+  static constexpr int KSTRIDE = D * 2 + 16;      // bytes; b128 row reads hit distinct banks
+  static constexpr int VSTRIDE = D * 2 + 64;      // bytes; 4-row transpose reads hit distinct banks
+  static constexpr int KBYTES = BN * KSTRIDE;
+  static constexpr int VBYTES = BN * VSTRIDE;
+  static constexpr int STAGE = KBYTES + VBYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int CHUNKS = BN * D * 2 / 16;  // 16-byte pieces per tensor tile
+  static constexpr int CPT = CHUNKS / 256;        // pieces per thread
+  static constexpr int CPR = D * 2 / 16;          // pieces per row
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
+  using C = FwdCfg<D>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int32_t s_unit;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int G = p.hq / p.hkv;
+
+  // unit numbering: with hq % 8 == 0 each XCD owns a contiguous eighth of the heads
+  const bool per_xcd = (p.hq % kNumXcd) == 0;
+  const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
+  const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
+  const int n_tiles = p.hdr_ro->n_tiles;
+  const int n_units = n_tiles * heads_here;
+
+  for (;;) {
+    if (tid == 0) s_unit = atomicAdd(&p.hdr->counter[xcd], 1);
+    __syncthreads();
+    const int unit = __builtin_amdgcn_readfirstlane(s_unit);
+    __syncthreads();
+    if (unit >= n_units) break;
+    const int tile_i = unit / heads_here;
+    const int head = xcd * heads_here + unit % heads_here;
+    const int kvh = head / G;
+    const Tile tile = p.tiles[tile_i];
+    const fcp_work_desc w = p.work[tile.work];
+
+    const int q_r0 = tile.idx * C::BM;                       // first row of the unit in the item
+    const int rows_here = min(C::BM, w.q_len - q_r0);
+    const int wave_r0 = q_r0 + wave * 32;
+    const bool wave_active = wave * 32 < rows_here;
+    const int my_row = wave_r0 + l32;
+    const bool row_valid = my_row < w.q_len;
+    const int row_ld = min(my_row, w.q_len - 1);
+    const int q_pos = w.q_seq_start + my_row;
+    const int wave_first_pos = w.q_seq_start + wave_r0;
+    const int wave_last_pos = w.q_seq_start + min(wave_r0 + 31, w.q_len - 1);
+
+    // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16*ks + 8*g2 + [0,8)
+    bf16x8 qf[D / 16];
+    {
+      const uint16_t* qp = p.q + ((int64_t)(w.q_local_off + row_ld) * p.hq + head) * D + 8 * g2;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    }
+
+    // visible key range per segment for this unit
+    const int last_pos = w.q_seq_start + q_r0 + rows_here - 1;
+    int vis[2], nt[2];
+    int64_t kv_row0[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      int vl = 0;
+      if (s < w.n_seg) vl = max(0, min(w.k_len[s], last_pos - w.k_seq_start[s] + 1));
+      vis[s] = vl;
+      nt[s] = (vl + C::BN - 1) / C::BN;
+      kv_row0[s] = (int64_t)p.cu[w.seq] + w.k_seq_start[s];
+    }
+    const int n_iter = nt[0] + nt[1];
+
+    f32x16 oacc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    float m_run = -INFINITY;   // running maximum in log2 units (score * scale_log2)
+    float l_run = 0.f;         // this lane's share of the running sum
+
+    // ---- K/V tile movement ---------------------------------------------------------
+    u32x4 kreg[C::CPT], vreg[C::CPT];
+    auto issue_loads = [&](int it) {
+      const int s = it >= nt[0] ? 1 : 0;
+      const int kt = it - (s ? nt[0] : 0);
+      const int vl = vis[s];
+#pragma unroll
+      for (int c = 0; c < C::CPT; ++c) {
+        const int piece = tid + 256 * c;
+        const int r = piece / C::CPR, col = piece % C::CPR;
+        const int key = min(kt * C::BN + r, vl - 1);          // clamp: masked anyway
+        const int64_t off = ((kv_row0[s] + key) * p.hkv + kvh) * D + col * 8;
+        kreg[c] = *reinterpret_cast<const u32x4*>(p.k + off);
+        vreg[c] = *reinterpret_cast<const u32x4*>(p.v + off);
+      }
+    };
+    auto store_tile = [&](int buf) {
+      unsigned char* kb = smem + buf * C::STAGE;
+      unsigned char* vb = kb + C::KBYTES;
+#pragma unroll
+      for (int c = 0; c < C::CPT; ++c) {
+        const int piece = tid + 256 * c;
+        const int r = piece / C::CPR, col = piece % C::CPR;
+        *reinterpret_cast<u32x4*>(kb + r * C::KSTRIDE + col * 16) = kreg[c];
+        *reinterpret_cast<u32x4*>(vb + r * C::VSTRIDE + col * 16) = vreg[c];
+      }
+    };
+
+    if (n_iter > 0) {
+      issue_loads(0);
+      store_tile(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_iter; ++it) {
+      const int buf = it & 1;
+      if (it + 1 < n_iter) issue_loads(it + 1);
+
+      const int s = it >= nt[0] ? 1 : 0;
+      const int kt = it - (s ? nt[0] : 0);
+      const int k_pos0 = w.k_seq_start[s] + kt * C::BN;       // position of the tile's first key
+      const int n_valid = min(C::BN, vis[s] - kt * C::BN);     // keys of the tile inside the segment
+      // wave-uniform: does this wave see anything in the tile / need the element mask?
+      const bool wave_sees = wave_active && k_pos0 <= wave_last_pos;
+      const bool need_mask = (k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN);
+
+      if (wave_sees) {
+        const unsigned char* kb = smem + buf * C::STAGE;
+        const unsigned char* vb = kb + C::KBYTES;
+        // ---- S^T[key, q] = K Q^T ------------------------------------------------------
+        f32x16 sacc[2];
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) sacc[kbk][i] = 0.f;
+          const unsigned char* krow = kb + (32 * kbk + l32) * C::KSTRIDE + 16 * g2;
+#pragma unroll
+          for (int ks = 0; ks < D / 16; ++ks) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
+            sacc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kbk], 0, 0, 0);
+          }
+        }
+        // ---- mask + online softmax ------------------------------------------------------
+        // register i of block kbk is key 32*kbk + 8*(i/4) + 4*g2 + (i%4) of the tile
+        if (need_mask) {
+#pragma unroll
+          for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const int kk = 32 * kbk + 8 * (i / 4) + 4 * g2 + (i % 4);
+              if (kk >= n_valid || k_pos0 + kk > q_pos) sacc[kbk][i] = -INFINITY;
+            }
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kbk][i]);
+        mx = lane32_partner_max(mx);
+        const float m_new = fmaxf(m_run, mx * p.scale_log2);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 pf[4];   // P^T as B operand: k-step t covers keys 16t..16t+15 of the tile
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(sacc[kbk][i], p.scale_log2, -m_use));
+            psum += e;
+            pf[2 * kbk + i / 8][i % 8] = (__bf16)e;
+          }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        // ---- O^T[d, q] += V^T P^T ---------------------------------------------------------
+        // A operand rows d = 32*db + l32; its 8 k-slots are keys 16t + {4*g2 + [0,4), 8 + 4*g2 + [0,4)}.
+        // Transpose read: lane supplies the address of row (l%16)/4, channels 4*(l%4) + [0,4) of its
+        // 16-lane block; block b covers channels 16*(b%2) + [0,16) for key group g2 = b/2.
+        const unsigned char* vbase = vb + (4 * g2 + ((lane & 15) >> 2)) * C::VSTRIDE +
+                                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            const unsigned char* a0 = vbase + (16 * t) * C::VSTRIDE + 64 * db;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(a0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(a0 + 8 * C::VSTRIDE));
+            const bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
+            const bf16x8 a = __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[t], oacc[db], 0, 0, 0);
+          }
+        }
+      }
+
+      if (it + 1 < n_iter) store_tile(buf ^ 1);
+      __syncthreads();
+    }
+
+    // ---- epilogue: normalise, write partial O (fp32) and LSE --------------------------------
+    const float l_tot = lane32_partner_sum(l_run);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    if (row_valid) {
+      float* orow = p.o_part + (int64_t)w.step * ((int64_t)p.tq * p.hq * D) +
+                    ((int64_t)(w.q_local_off + my_row) * p.hq + head) * D;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 o4 = {oacc[db][4 * r4] * inv, oacc[db][4 * r4 + 1] * inv, oacc[db][4 * r4 + 2] * inv,
+                      oacc[db][4 * r4 + 3] * inv};
+          *reinterpret_cast<f32x4*>(orow + 32 * db + 8 * r4 + 4 * g2) = o4;
+        }
+      if (g2 == 0) {
+        const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+        p.lse_part[(int64_t)w.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + w.q_local_off + my_row] = lse;
+      }
+    }
+  }
+}
+
+}  // namespace
+}  // namespace fcp
+
+using fcp::fail;
+
+extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                                 int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                                 int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                                 float softmax_scale, float* o_part, float* lse_part, void* scratch,
+                                 size_t scratch_bytes, void* stream) {
+  fcp::clear_error();
+  if (!q || !k || !v || !cu_seqlens_kv || !o_part || !lse_part || !scratch)
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: null pointer");
+  if (n_work > 0 && !work) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: work is NULL");
+  if (tq < 0 || tkv < 1 || n_seqs < 1 || n_work < 0 || n_parts < 1 || hq < 1 || hkv < 1)
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: bad sizes");
+  if (n_work > (1 << 24)) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: more than 2^24 work items");
+  if (hq % hkv != 0) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: hq %d not a multiple of hkv %d", hq, hkv);
+  if (head_dim != 64 && head_dim != 128) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: head_dim %d not 64/128", head_dim);
+  if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: softmax_scale must be positive and finite");
+  const uintptr_t align_mask = reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
+                               reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(o_part);
+  if (align_mask & 15u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: q/k/v/o_part must be 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(scratch) & 63u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: scratch must be 64-byte aligned");
+  const size_t need = fcp_scratch_bytes(FCP_SCRATCH_FWD, tq, tkv, hq, hkv, head_dim, n_work, n_parts);
+  if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_fwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
+  if ((int64_t)tq * hq * head_dim * (int64_t)n_parts > ((int64_t)1 << 40))
+    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: partial output too large");
+
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t cap = fcp::fwd_tile_cap(tq, n_work, n_parts);
+  if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
+  int rc = fcp::launch_schedule(false, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
+                                lse_part, (int64_t)n_parts * hq * tq, st);
+  if (rc != FCP_OK) return rc;
+  if (tq == 0 || n_work == 0) return FCP_OK;
+
+  fcp::FwdParams p;
+  p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v;
+  p.cu = cu_seqlens_kv; p.work = work;
+  p.hdr_ro = fcp::sched_header(scratch); p.hdr = (fcp::SchedHeader*)scratch;
+  p.tiles = fcp::sched_tiles(scratch, n_work);
+  p.o_part = o_part; p.lse_part = lse_part;
+  p.tq = tq; p.hq = hq; p.hkv = hkv;
+  p.scale_log2 = softmax_scale * 1.4426950408889634f;
+
+  int dev = 0, n_cu = 256;
+  FCP_HIP_CHECK(hipGetDevice(&dev));
+  FCP_HIP_CHECK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  int64_t units = cap * hq;
+  int64_t blocks = (int64_t)n_cu * 2;
+  if (blocks > units) blocks = (units + 7) / 8 * 8;   // keep a multiple of the XCD count
+  if (blocks < 8) blocks = 8;
+  if (head_dim == 128) {
+    static bool attr_done = false;
+    if (!attr_done) {
+      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::fwd_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        fcp::FwdCfg<128>::LDS_BYTES));
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(fcp::fwd_kernel<128>, dim3((unsigned)blocks), dim3(256), fcp::FwdCfg<128>::LDS_BYTES, st, p);
+  } else {
+    static bool attr_done = false;
+    if (!attr_done) {
+      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::fwd_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        fcp::FwdCfg<64>::LDS_BYTES));
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(fcp::fwd_kernel<64>, dim3((unsigned)blocks), dim3(256), fcp::FwdCfg<64>::LDS_BYTES, st, p);
+  }
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}

@@ -1,0 +1,62 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "fcp.h"
+
+namespace fcp {
+
+// Records a thread-local error message and returns `code`.
+int fail(int code, const char* fmt, ...);
+void clear_error();
+
+#define FCP_HIP_CHECK(expr)                                                          \
+  do {                                                                               \
+    hipError_t e__ = (expr);                                                         \
+    if (e__ != hipSuccess)                                                           \
+      return ::fcp::fail(FCP_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
+  } while (0)
+
+// ---- device-side schedule kept at the start of the caller's scratch buffer ----------
+// Both attention kernels are persistent: blocks pull (tile, head) units from counters
+// until the list is exhausted.  There is one counter per XCD so that the blocks of one
+// XCD (blockIdx % 8) walk the heads of the same KV heads and share K/V in that XCD's L2.
+constexpr int kNumXcd = 8;
+struct SchedHeader {
+  int32_t n_tiles;              // tiles in the list (sorted by decreasing cost)
+  int32_t n_rejected;           // work items that failed validation
+  int32_t max_cost;
+  int32_t pad0;
+  int32_t counter[kNumXcd];     // next unit per XCD (or counter[0] alone)
+  int32_t pad1[4];
+};                               // 64 bytes
+static_assert(sizeof(SchedHeader) == 64, "header size");
+
+struct Tile {                    // forward: a block of query rows of one work item
+  int32_t work;                  // backward: a block of keys of one segment of one work item
+  int32_t idx;                   // fwd: q-tile index; bwd: (seg << 24) | kv-tile index
+};
+
+constexpr int kFwdBM = 128;      // query rows per forward tile
+constexpr int kFwdBN = 64;       // keys per forward inner step
+constexpr int kBwdBN = 128;      // keys per backward tile
+constexpr int kBwdBM = 32;       // query rows per backward inner step
+
+int64_t fwd_tile_cap(int32_t tq, int64_t n_work, int32_t n_parts);
+int64_t bwd_tile_cap(int32_t tkv, int64_t n_work);
+
+// scratch layout: SchedHeader | item offsets int32[n_work+1] (padded to 64 B) | Tile[cap]
+size_t sched_item_off_bytes(int64_t n_work);
+inline const SchedHeader* sched_header(const void* scratch) { return static_cast<const SchedHeader*>(scratch); }
+inline const Tile* sched_tiles(const void* scratch, int64_t n_work) {
+  return reinterpret_cast<const Tile*>(static_cast<const char*>(scratch) + sizeof(SchedHeader) +
+                                       sched_item_off_bytes(n_work));
+}
+
+// Builds the tile list for a launch and (forward) fills lse_part with -inf.
+int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
+                    const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
+                    int32_t n_parts, int64_t tile_cap, void* scratch, float* lse_fill,
+                    int64_t lse_fill_n, hipStream_t stream);
+
+}  // namespace fcp

@@ -1,0 +1,177 @@
+// Bandwidth-bound row kernels: log-sum-exp merge of the ring-step partials, the backward
+// prologue delta = rowsum(dO * O), and the fp32 -> bf16 cast of the gradient accumulators.
+//
+// The paper computes attention (Eq. 1) ring-style over a CP group (Sec. 3.2); each ring
+// step sees a different key set, so its softmax is normalised locally and the per-step
+// results are combined exactly by weighting with exp(LSE_s - LSE).
+#include "fcp_internal.h"
+
+namespace fcp {
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ inline uint32_t bf16_rne(float f) {           // one bf16 in the low 16 bits
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0u;   // NaN
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+__device__ inline uint32_t pack_bf16(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
+__device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+constexpr int kMaxParts = 16;   // partial slots held in registers by one merge thread
+constexpr int kRowsPerBlock = 16;
+
+// One thread owns 8 consecutive channels of one (row, head); D/8 threads per (row, head);
+// a 256-thread block covers kRowsPerBlock*16/(D/8)... rows of ONE head so that the LSE reads
+// (head-major) are contiguous.
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(const float* __restrict__ o_part,
+                                                    const float* __restrict__ lse_part, int n_parts,
+                                                    int tq, int hq, uint32_t* __restrict__ o,
+                                                    float* __restrict__ lse) {
+  constexpr int TPR = D / 8;              // threads per (row, head)
+  constexpr int ROWS = 256 / TPR;         // rows per block
+  const int h = blockIdx.y;
+  const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
+  const int c8 = threadIdx.x % TPR;
+  if (row >= tq) return;
+  const int64_t lse_stride = (int64_t)hq * tq;
+  const int64_t o_stride = (int64_t)tq * hq * D;
+  float ls[kMaxParts];
+  float m = -INFINITY;
+#pragma unroll
+  for (int p = 0; p < kMaxParts; ++p) {
+    ls[p] = p < n_parts ? lse_part[p * lse_stride + (int64_t)h * tq + row] : -INFINITY;
+    m = fmaxf(m, ls[p]);
+  }
+  const float m_safe = m == -INFINITY ? 0.f : m;
+  float tot = 0.f;
+#pragma unroll
+  for (int p = 0; p < kMaxParts; ++p) {
+    ls[p] = __expf(ls[p] - m_safe);       // exp(-inf) = 0
+    tot += ls[p];
+  }
+  const float inv = tot > 0.f ? 1.f / tot : 0.f;
+  f32x4 a0 = {0, 0, 0, 0}, a1 = {0, 0, 0, 0};
+  const int64_t off = ((int64_t)row * hq + h) * D + c8 * 8;
+#pragma unroll
+  for (int p = 0; p < kMaxParts; ++p) {
+    if (p < n_parts && ls[p] > 0.f) {     // skipped slots are never read
+      const f32x4* src = reinterpret_cast<const f32x4*>(o_part + p * o_stride + off);
+      const float w = ls[p] * inv;
+      const f32x4 x0 = __builtin_nontemporal_load(src), x1 = __builtin_nontemporal_load(src + 1);
+      a0 += w * x0;
+      a1 += w * x1;
+    }
+  }
+  u32x4 out = {pack_bf16(a0[0], a0[1]), pack_bf16(a0[2], a0[3]), pack_bf16(a1[0], a1[1]), pack_bf16(a1[2], a1[3])};
+  *reinterpret_cast<u32x4*>(o + off / 2) = out;
+  if (c8 == 0) lse[(int64_t)h * tq + row] = tot > 0.f ? m_safe + __logf(tot) : -INFINITY;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void delta_kernel(const uint32_t* __restrict__ o,
+                                                    const uint32_t* __restrict__ d_o, int tq, int hq,
+                                                    float* __restrict__ delta) {
+  constexpr int TPR = D / 8;
+  constexpr int ROWS = 256 / TPR;
+  const int h = blockIdx.y;
+  const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
+  const int c8 = threadIdx.x % TPR;
+  float s = 0.f;
+  if (row < tq) {
+    const int64_t off = (((int64_t)row * hq + h) * D + c8 * 8) / 2;
+    const u32x4 a = *reinterpret_cast<const u32x4*>(o + off);
+    const u32x4 b = *reinterpret_cast<const u32x4*>(d_o + off);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s += bf16_lo(a[i]) * bf16_lo(b[i]) + bf16_hi(a[i]) * bf16_hi(b[i]);
+  }
+#pragma unroll
+  for (int off = TPR / 2; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+  if (row < tq && c8 == 0) delta[(int64_t)h * tq + row] = s;
+}
+
+__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ acc,
+                                                       uint32_t* __restrict__ out, int64_t n8,
+                                                       int64_t n) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+    const f32x4* src = reinterpret_cast<const f32x4*>(acc) + 2 * i;
+    const f32x4 x0 = src[0], x1 = src[1];
+    u32x4 r = {pack_bf16(x0[0], x0[1]), pack_bf16(x0[2], x0[3]), pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+    reinterpret_cast<u32x4*>(out)[i] = r;
+  }
+  // tail (n not a multiple of 8): single elements, one thread
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    uint16_t* o16 = reinterpret_cast<uint16_t*>(out);
+    for (int64_t i = n8 * 8; i < n; ++i) o16[i] = (uint16_t)bf16_rne(acc[i]);
+  }
+}
+
+}  // namespace
+}  // namespace fcp
+
+using fcp::fail;
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+extern "C" int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
+                             int32_t hq, int32_t head_dim, void* o, float* lse, void* stream) {
+  fcp::clear_error();
+  if (!o_part || !lse_part || !o || !lse) return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge: null pointer");
+  if (tq < 0 || hq < 1 || n_parts < 1) return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge: bad sizes");
+  if (n_parts > fcp::kMaxParts) return fail(FCP_ERR_UNSUPPORTED, "fcp_lse_merge: n_parts %d > %d", n_parts, fcp::kMaxParts);
+  if (head_dim != 64 && head_dim != 128) return fail(FCP_ERR_UNSUPPORTED, "fcp_lse_merge: head_dim %d not 64/128", head_dim);
+  if (hq > 65535) return fail(FCP_ERR_UNSUPPORTED, "fcp_lse_merge: hq > 65535");
+  if (!aligned16(o_part) || !aligned16(o)) return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge: o_part/o must be 16-byte aligned");
+  if (tq == 0) return FCP_OK;
+  hipStream_t st = (hipStream_t)stream;
+  if (head_dim == 128) {
+    dim3 grid((tq + 15) / 16, hq);
+    hipLaunchKernelGGL(fcp::merge_kernel<128>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse);
+  } else {
+    dim3 grid((tq + 31) / 32, hq);
+    hipLaunchKernelGGL(fcp::merge_kernel<64>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse);
+  }
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}
+
+extern "C" int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, int32_t head_dim,
+                                  float* delta, void* stream) {
+  fcp::clear_error();
+  if (!o || !d_o || !delta) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_delta: null pointer");
+  if (tq < 0 || hq < 1 || hq > 65535) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_delta: bad sizes");
+  if (head_dim != 64 && head_dim != 128) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_delta: head_dim %d not 64/128", head_dim);
+  if (!aligned16(o) || !aligned16(d_o)) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_delta: o/d_o must be 16-byte aligned");
+  if (tq == 0) return FCP_OK;
+  hipStream_t st = (hipStream_t)stream;
+  if (head_dim == 128) {
+    dim3 grid((tq + 15) / 16, hq);
+    hipLaunchKernelGGL(fcp::delta_kernel<128>, grid, dim3(256), 0, st, (const uint32_t*)o, (const uint32_t*)d_o, tq, hq, delta);
+  } else {
+    dim3 grid((tq + 31) / 32, hq);
+    hipLaunchKernelGGL(fcp::delta_kernel<64>, grid, dim3(256), 0, st, (const uint32_t*)o, (const uint32_t*)d_o, tq, hq, delta);
+  }
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}
+
+extern "C" int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, void* stream) {
+  fcp::clear_error();
+  if (!acc || !out_bf16) return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize: null pointer");
+  if (n < 0) return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize: n < 0");
+  if (!aligned16(acc) || !aligned16(out_bf16)) return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize: pointers must be 16-byte aligned");
+  if (n == 0) return FCP_OK;
+  const int64_t n8 = n / 8;
+  int64_t blocks = (n8 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(fcp::finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, acc,
+                     (uint32_t*)out_bf16, n8, n);
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}

@@ -1,0 +1,270 @@
+// Device-side tile scheduler for the attention kernels.
+//
+// The paper's motivation (Sec. 4.1) is that heterogeneous lengths leave some compute units
+// as stragglers; inside one rank the same holds for tiles: a query block at the end of a long
+// chunk has hundreds of key blocks, one from a short sequence has one.  This kernel turns the
+// rank's work items (device memory) into a list of tiles sorted by DECREASING cost, which the
+// persistent attention kernels pull from shared counters (longest-first list scheduling).
+// Fully masked key blocks never enter the cost or the kernels' loops.
+//
+// It also validates every work item against the extents the caller passed, so that no
+// attention kernel can be steered out of bounds by a bad descriptor: a rejected item gets
+// no tiles and is counted in the header.
+#include "fcp_internal.h"
+
+namespace fcp {
+
+namespace {
+
+constexpr int kSchedThreads = 1024;
+constexpr int kBuckets = 2048;
+
+struct ItemInfo {
+  bool ok;
+  int32_t n_tiles;     // tiles this item contributes
+  int32_t nt0;         // backward: tiles of segment 0
+  int32_t max_cost;
+};
+
+__device__ inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
+
+__device__ inline bool item_valid(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
+                                  int32_t tq, int32_t tkv, int32_t n_parts, bool backward) {
+  if (w.seq < 0 || w.seq >= n_seqs) return false;
+  if (!backward && (w.step < 0 || w.step >= n_parts)) return false;
+  if (w.q_len < 1 || w.q_local_off < 0 || w.q_seq_start < 0) return false;
+  if ((int64_t)w.q_local_off + w.q_len > (int64_t)tq) return false;
+  if ((int64_t)w.q_seq_start + w.q_len > (int64_t)(1 << 30)) return false;
+  if (w.n_seg < 1 || w.n_seg > 2) return false;
+  const int64_t s0 = cu[w.seq], s1 = cu[w.seq + 1];
+  if (s0 < 0 || s1 < s0 || s1 > (int64_t)tkv) return false;
+  for (int s = 0; s < w.n_seg; ++s) {
+    if (w.k_seq_start[s] < 0 || w.k_len[s] < 1) return false;
+    if (s0 + (int64_t)w.k_seq_start[s] + w.k_len[s] > s1) return false;
+  }
+  return true;
+}
+
+// keys of segment s that at least one row of [row0, row1) of the item can see
+__device__ inline int32_t visible_len(const fcp_work_desc& w, int s, int32_t last_row) {
+  const int64_t last_q_pos = (int64_t)w.q_seq_start + last_row;
+  int64_t v = last_q_pos - w.k_seq_start[s] + 1;
+  if (v < 0) v = 0;
+  if (v > w.k_len[s]) v = w.k_len[s];
+  return (int32_t)v;
+}
+
+__device__ inline int32_t fwd_cost(const fcp_work_desc& w, int32_t qt) {
+  int32_t last_row = min((qt + 1) * kFwdBM, w.q_len) - 1;
+  int32_t c = 0;
+  for (int s = 0; s < w.n_seg; ++s) c += ceil_div(visible_len(w, s, last_row), kFwdBN);
+  return c;
+}
+
+// backward: cost of key tile kt of segment s = query blocks that see its first key
+__device__ inline int32_t bwd_cost(const fcp_work_desc& w, int s, int32_t kt) {
+  const int64_t first_k_pos = (int64_t)w.k_seq_start[s] + (int64_t)kt * kBwdBN;
+  int64_t first_row = first_k_pos - w.q_seq_start;
+  if (first_row < 0) first_row = 0;
+  const int64_t rows = (int64_t)w.q_len - first_row;
+  return rows <= 0 ? 0 : (int32_t)((rows + kBwdBM - 1) / kBwdBM);
+}
+
+__device__ inline ItemInfo item_info(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
+                                     int32_t tq, int32_t tkv, int32_t n_parts, bool backward) {
+  ItemInfo r{false, 0, 0, 0};
+  r.ok = item_valid(w, cu, n_seqs, tq, tkv, n_parts, backward);
+  if (!r.ok) return r;
+  if (!backward) {
+    r.n_tiles = ceil_div(w.q_len, kFwdBM);
+    r.max_cost = fwd_cost(w, r.n_tiles - 1);
+  } else {
+    r.nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), kBwdBN);
+    int32_t nt1 = w.n_seg > 1 ? ceil_div(visible_len(w, 1, w.q_len - 1), kBwdBN) : 0;
+    r.n_tiles = r.nt0 + nt1;
+    r.max_cost = ceil_div(w.q_len, kBwdBM);
+  }
+  return r;
+}
+
+// Exclusive block scan of one value per thread; returns the exclusive prefix and sets
+// `total` (same for every thread).  `s_wave` holds one slot per wave.
+__device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32_t& total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int32_t inc = v;
+  for (int off = 1; off < 64; off <<= 1) {
+    int32_t t = __shfl_up(inc, off, 64);
+    if (lane >= off) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) s_wave[wave] = inc;
+  __syncthreads();
+  int32_t base = 0, tot = 0;
+  for (int w = 0; w < kSchedThreads / 64; ++w) {
+    const int32_t x = s_wave[w];
+    if (w < wave) base += x;
+    tot += x;
+  }
+  total = tot;
+  return base + inc - v;
+}
+
+__global__ __launch_bounds__(kSchedThreads) void sched_kernel(
+    int backward, const fcp_work_desc* __restrict__ work, int32_t n_work,
+    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
+    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, Tile* tiles, float* lse_fill,
+    int64_t lse_fill_n) {
+  if (blockIdx.x > 0) {  // the other blocks pre-fill the partial LSE with -inf
+    const int64_t stride = (int64_t)(gridDim.x - 1) * kSchedThreads;
+    for (int64_t i = (int64_t)(blockIdx.x - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
+      lse_fill[i] = -INFINITY;
+    return;
+  }
+  __shared__ int32_t s_wave[kSchedThreads / 64];
+  __shared__ int32_t s_hist[kBuckets];
+  __shared__ int32_t s_max, s_rej, s_carry;
+  const int tid = threadIdx.x;
+  if (tid == 0) { s_max = 0; s_rej = 0; s_carry = 0; }
+  for (int b = tid; b < kBuckets; b += kSchedThreads) s_hist[b] = 0;
+  __syncthreads();
+
+  // Pass 1: validate, count tiles per item, exclusive offsets into item_off[0..n_work].
+  for (int32_t base = 0; base < n_work; base += kSchedThreads) {
+    const int32_t i = base + tid;
+    int32_t cnt = 0;
+    if (i < n_work) {
+      const fcp_work_desc w = work[i];
+      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0);
+      if (!info.ok) atomicAdd(&s_rej, 1);
+      cnt = info.n_tiles;
+      if (info.max_cost > 0) atomicMax(&s_max, info.max_cost);
+    }
+    int32_t total;
+    const int32_t ex = block_exclusive_scan(cnt, s_wave, total);
+    const int32_t carry = s_carry;
+    if (i < n_work) item_off[i] = carry + ex;
+    __syncthreads();
+    if (tid == 0) s_carry = carry + total;
+    __syncthreads();
+  }
+  const int32_t total_tiles = s_carry;
+  const int32_t n_tiles = min(total_tiles, tile_cap);
+  if (tid == 0) {
+    item_off[n_work] = total_tiles;
+    if (total_tiles > tile_cap) atomicAdd(&s_rej, total_tiles - tile_cap);
+  }
+  int shift = 0;
+  while ((s_max >> shift) >= kBuckets) ++shift;
+  __syncthreads();
+
+  // Pass 2 and 3 share the decode of a flat tile number into (item, index, cost).
+  auto decode = [&](int32_t t, Tile& out) -> int32_t {
+    int32_t lo = 0, hi = n_work - 1;               // last item with item_off <= t
+    while (lo < hi) {
+      const int32_t mid = (lo + hi + 1) >> 1;
+      if (item_off[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    const fcp_work_desc w = work[lo];
+    const int32_t local = t - item_off[lo];
+    out.work = lo;
+    if (!backward) {
+      out.idx = local;
+      return fwd_cost(w, local);
+    }
+    const int32_t nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), kBwdBN);
+    const int s = local >= nt0 ? 1 : 0;
+    const int32_t kt = local - (s ? nt0 : 0);
+    out.idx = (s << 24) | kt;
+    return bwd_cost(w, s, kt);
+  };
+
+  for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
+    Tile tl;
+    const int32_t c = decode(t, tl);
+    atomicAdd(&s_hist[min(c >> shift, kBuckets - 1)], 1);
+  }
+  __syncthreads();
+  // Descending-cost start offset of every bucket: scan the histogram from the top.
+  {
+    static_assert(kBuckets == 2 * kSchedThreads, "two buckets per thread");
+    const int b_hi = kBuckets - 1 - 2 * tid, b_lo = b_hi - 1;
+    const int32_t h_hi = s_hist[b_hi], h_lo = s_hist[b_lo];
+    int32_t total;
+    const int32_t ex = block_exclusive_scan(h_hi + h_lo, s_wave, total);
+    __syncthreads();
+    s_hist[b_hi] = ex;
+    s_hist[b_lo] = ex + h_hi;
+  }
+  __syncthreads();
+  for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
+    Tile tl;
+    const int32_t c = decode(t, tl);
+    const int32_t pos = atomicAdd(&s_hist[min(c >> shift, kBuckets - 1)], 1);
+    tiles[pos] = tl;
+  }
+  if (tid == 0) {
+    hdr->n_tiles = n_tiles;
+    hdr->n_rejected = s_rej;
+    hdr->max_cost = s_max;
+    hdr->pad0 = 0;
+    for (int c = 0; c < kNumXcd; ++c) hdr->counter[c] = 0;
+  }
+}
+
+}  // namespace
+
+int64_t fwd_tile_cap(int32_t tq, int64_t n_work, int32_t n_parts) {
+  return n_work + (int64_t)n_parts * ((tq + kFwdBM - 1) / kFwdBM);
+}
+
+int64_t bwd_tile_cap(int32_t tkv, int64_t n_work) {
+  // per sequence the key segments of one rank's items add up to at most twice its length
+  return 2 * n_work + 2 * (int64_t)((tkv + kBwdBN - 1) / kBwdBN);
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+size_t sched_item_off_bytes(int64_t n_work) { return align_up((size_t)(n_work + 1) * sizeof(int32_t), 64); }
+
+int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
+                    const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
+                    int32_t n_parts, int64_t tile_cap, void* scratch, float* lse_fill,
+                    int64_t lse_fill_n, hipStream_t stream) {
+  char* base = static_cast<char*>(scratch);
+  SchedHeader* hdr = reinterpret_cast<SchedHeader*>(base);
+  int32_t* item_off = reinterpret_cast<int32_t*>(base + sizeof(SchedHeader));
+  Tile* tiles = reinterpret_cast<Tile*>(base + sizeof(SchedHeader) + sched_item_off_bytes(n_work));
+  int fill_blocks = 0;
+  if (lse_fill && lse_fill_n > 0) {
+    fill_blocks = (int)((lse_fill_n + kSchedThreads * 4 - 1) / (kSchedThreads * 4));
+    if (fill_blocks > 1024) fill_blocks = 1024;
+    if (fill_blocks < 1) fill_blocks = 1;
+  }
+  hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks), dim3(kSchedThreads), 0, stream,
+                     backward ? 1 : 0, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
+                     (int32_t)tile_cap, hdr, item_off, tiles, lse_fill, lse_fill_n);
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}
+
+}  // namespace fcp
+
+extern "C" size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t hq, int32_t hkv,
+                                    int32_t head_dim, int64_t n_work, int32_t n_parts) {
+  (void)hq; (void)hkv; (void)head_dim;
+  if (tq < 0 || tkv < 0 || n_work < 0 || n_parts < 0) return 0;
+  const int64_t cap = which == FCP_SCRATCH_BWD ? fcp::bwd_tile_cap(tkv, n_work)
+                                               : fcp::fwd_tile_cap(tq, n_work, n_parts);
+  return sizeof(fcp::SchedHeader) + fcp::sched_item_off_bytes(n_work) + (size_t)cap * sizeof(fcp::Tile) + 256;
+}
+
+extern "C" int fcp_scratch_status(const void* scratch, void* stream, int32_t* n_tiles, int32_t* n_rejected) {
+  fcp::clear_error();
+  if (!scratch) return fcp::fail(FCP_ERR_INVALID_ARG, "fcp_scratch_status: scratch is NULL");
+  fcp::SchedHeader h;
+  FCP_HIP_CHECK(hipMemcpyAsync(&h, scratch, sizeof(h), hipMemcpyDeviceToHost, (hipStream_t)stream));
+  FCP_HIP_CHECK(hipStreamSynchronize((hipStream_t)stream));
+  if (n_tiles) *n_tiles = h.n_tiles;
+  if (n_rejected) *n_rejected = h.n_rejected;
+  return FCP_OK;
+}

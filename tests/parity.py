@@ -1,0 +1,77 @@
+"""Helpers of the GPU parity tests: run one rank on the GPU through the C ABI and the
+oracle on the CPU for the same seeded inputs, and compare to the stated tolerances.
+
+Tolerances (the build's target statement): max|x_gpu - x_ref| / max|x_ref| <= 2e-2 for the
+bf16 tensors O, dQ, dK, dV; max|LSE_gpu - LSE_ref| <= 1e-3 (absolute) for fp32 LSE.
+"""
+import numpy as np
+
+import fcp_synth as synth
+from oracle import attn as oattn
+from oracle import plan as oplan
+
+TOL_BF16_REL = 2e-2
+TOL_LSE_ABS = 1e-3
+
+
+def rel_err(got, ref):
+    ref = np.asarray(ref, np.float64)
+    got = np.asarray(got, np.float64)
+    denom = np.abs(ref).max()
+    return float(np.abs(got - ref).max() / (denom if denom > 0 else 1.0))
+
+
+def bf16_tensor_to_f64(t):
+    import torch
+    return synth.bf16_bits_to_f64(t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
+
+
+def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label=""):
+    """Full element-by-element comparison of one rank (small workloads)."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
+    ochunks, owork = oplan.shard_plan(wl.seq_lens, wl.cp_degree)
+    assert ra.chunks.tobytes() == ochunks.tobytes() and ra.work_all.tobytes() == owork.tobytes()
+    rows = oplan.rank_rows(ochunks, wl.cu_seqlens, rank)
+    if len(rows) == 0:
+        return None
+    ra.set_inputs(q, k, v, do if backward else None)
+    ra.forward()
+    torch.cuda.synchronize()
+    n_tiles, n_rej = __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_f)
+    assert n_rej == 0, f"{label}: {n_rej} work items rejected"
+    O_ref, LSE_ref = oattn.attn_fwd(q, k, v, wl.cu_seqlens, wl.softmax_scale, rows)
+    O = bf16_tensor_to_f64(ra.o)
+    LSE = ra.lse.cpu().numpy().astype(np.float64).T          # [tq, hq]
+    res = {"O": rel_err(O, O_ref), "LSE": float(np.abs(LSE - LSE_ref).max())}
+    assert np.isfinite(O).all() and np.isfinite(LSE).all(), label
+    assert res["O"] <= TOL_BF16_REL, (label, res)
+    assert res["LSE"] <= TOL_LSE_ABS, (label, res)
+    if check_partials:
+        qf, kf, vf = (synth.bf16_bits_to_f64(x) for x in (q, k, v))
+        Op_ref, Lp_ref = oplan.rank_partials(qf, kf, vf, wl.cu_seqlens, ochunks, owork, rank, wl.softmax_scale)
+        Op = ra.o_part.cpu().numpy().astype(np.float64)
+        Lp = ra.lse_part.cpu().numpy().astype(np.float64).transpose(0, 2, 1)
+        assert Op.shape == Op_ref.shape
+        fin = np.isfinite(Lp_ref)
+        assert (np.isneginf(Lp) == ~fin).all(), label          # uncovered rows are -inf, exactly those
+        assert np.abs(Lp[fin] - Lp_ref[fin]).max() <= TOL_LSE_ABS, label
+        err = np.abs(np.where(fin[..., None], Op - Op_ref, 0.0)).max() / np.abs(Op_ref).max()
+        assert err <= TOL_BF16_REL, (label, err)
+        res["O_part"] = float(err)
+    if backward:
+        ra.backward()
+        torch.cuda.synchronize()
+        n_tiles, n_rej = __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_b)
+        assert n_rej == 0, f"{label}: {n_rej} work items rejected (bwd)"
+        dQ_ref = oattn.attn_dq(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref)
+        dK_ref, dV_ref = oattn.attn_dkv(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref)
+        got = {"dQ": bf16_tensor_to_f64(ra.dq), "dK": bf16_tensor_to_f64(ra.dk), "dV": bf16_tensor_to_f64(ra.dv)}
+        for name, ref in (("dQ", dQ_ref), ("dK", dK_ref), ("dV", dV_ref)):
+            assert np.isfinite(got[name]).all(), (label, name)
+            res[name] = rel_err(got[name], ref)
+            assert res[name] <= TOL_BF16_REL, (label, name, res)
+        res["_dK_acc"] = ra.dk_acc.cpu().numpy().astype(np.float64)
+        res["_dV_acc"] = ra.dv_acc.cpu().numpy().astype(np.float64)
+    return res

@@ -1,0 +1,79 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by
+element, on seeded inputs that span several tiles, ragged tails and every CP degree 1..8."""
+import numpy as np
+import pytest
+
+import fcp_synth as synth
+from oracle import attn as oattn
+
+from parity import TOL_BF16_REL, check_rank, rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def test_cfg0_single_sequence_d64_forward():
+    wl = synth.make_workload(0)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    _say("cfg0 L=512 d=1 h4x4 D=64 fwd")
+    res = check_rank(wl, q, k, v, None, 0, backward=False, check_partials=True, label="cfg0")
+    _say(f"  {res}")
+
+
+def test_cfg1_L4096_degree3_rank1_fwd_bwd():
+    wl = synth.make_workload(1)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    _say("cfg1 L=4096 d=3 rank1 h8x8 D=128 fwd+bwd")
+    res = check_rank(wl, q, k, v, do, 1, backward=True, check_partials=True, label="cfg1")
+    _say("  " + str({a: b for a, b in res.items() if not a.startswith("_")}))
+
+
+@pytest.mark.parametrize("d", range(1, 9))
+def test_every_degree_all_ranks(d):
+    """One odd-length sequence at degree d packed with a short degree-1 sequence; every rank is
+    checked, and the ranks' dK/dV partial sums add up to the unsharded gradient."""
+    L = 997 + 13 * d
+    wl = synth.custom_workload([L, 75], [d, 1], hq=4, hkv=2, head_dim=128, seed=100 + d)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    dK_sum = dV_sum = None
+    for r in range(d):
+        _say(f"degree {d} rank {r} L={L}")
+        res = check_rank(wl, q, k, v, do, r, backward=True, check_partials=(r == d - 1), label=f"d{d}r{r}")
+        dK_sum = res["_dK_acc"] if dK_sum is None else dK_sum + res["_dK_acc"]
+        dV_sum = res["_dV_acc"] if dV_sum is None else dV_sum + res["_dV_acc"]
+    _, dK_ref, dV_ref = oattn.attn_bwd(q, k, v, do, wl.cu_seqlens, wl.softmax_scale)
+    assert rel_err(dK_sum, dK_ref) <= TOL_BF16_REL and rel_err(dV_sum, dV_ref) <= TOL_BF16_REL
+
+
+@pytest.mark.parametrize("hq,hkv,D", [(10, 2, 128), (4, 4, 64), (6, 2, 64), (8, 1, 128)])
+def test_head_layouts(hq, hkv, D):
+    """Grouped heads incl. ratio 5 (not a power of two), head counts that are / are not a
+    multiple of 8, both head dims."""
+    wl = synth.custom_workload([300, 1, 129, 64, 517], [2, 1, 1, 1, 3], hq=hq, hkv=hkv, head_dim=D, seed=7)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    for r in range(3):
+        _say(f"heads {hq}/{hkv} D={D} rank {r}")
+        check_rank(wl, q, k, v, do, r, backward=True, check_partials=True, label=f"h{hq}x{hkv}D{D}r{r}")
+
+
+def test_degenerate_lengths():
+    """Length 1, lengths below 2d (empty chunks), exact tile multiples, tile multiple +- 1."""
+    lens = [1, 5, 128, 127, 129, 64, 65, 3, 256, 2]
+    deg = [1, 4, 1, 1, 2, 1, 1, 2, 2, 1]
+    wl = synth.custom_workload(lens, deg, hq=8, hkv=2, head_dim=128, seed=21)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    for r in range(4):
+        _say(f"degenerate lengths rank {r}")
+        check_rank(wl, q, k, v, do, r, backward=True, check_partials=True, label=f"degenerate r{r}")
+
+
+def test_many_short_sequences():
+    rng = np.random.default_rng(5)
+    lens = rng.integers(1, 200, size=40)
+    wl = synth.custom_workload(lens, np.ones(40, np.int32), hq=8, hkv=8, head_dim=128, seed=22)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    _say("40 short sequences, degree 1")
+    check_rank(wl, q, k, v, do, 0, backward=True, label="shorts")

@@ -224,6 +224,10 @@ def test_row_subset_and_rank_partial_sum():
     np.testing.assert_array_equal(dQA, dQ[A])
     np.testing.assert_allclose(dKA + dKB, dK, rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(dVA + dVB, dV, rtol=1e-12, atol=1e-13)
+    # a key subset is the same rows of the full result
+    keys = np.array([31, 0, 7, 19], np.int64)
+    dKs, dVs = oattn.attn_dkv(q, k, v, do, cu, 0.3, A, OA, LA, keys=keys)
+    np.testing.assert_array_equal(dKs, dKA[keys]); np.testing.assert_array_equal(dVs, dVA[keys])
 
 
 def test_bf16_roundtrip_and_rne():
