@@ -1,0 +1,143 @@
+#!/usr/bin/env python3
+"""Benchmark of the FCP rank-local attention hot path on one MI355X.
+
+A "step" is one pass of the whole path for the reported rank of the workload:
+  fcp_attn_fwd_step (all ring steps) -> fcp_lse_merge -> zero grads -> fcp_attn_bwd_delta ->
+  fcp_attn_bwd_step (all ring steps) -> fcp_grad_finalize x3,
+with every input already resident in HBM.  The metric is causal-effective TFLOP/s:
+14 * pairs * head_dim * hq / time (4 forward + 10 backward flops per visible pair, channel
+and head; masked pairs are not counted).
+
+Prints ONE JSON line (see the keys below); `roofline` is for the dominant kernel (the
+backward step), `cpu_baseline` times the fp64 CPU oracle on a bounded sample of the same
+workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30):
+    """Times the oracle (as it stands) on a bounded sample: one KV-head group (hq/hkv query
+    heads + 1 KV head) and every `stride`-th of the rank's rows; forward, dQ and the dK/dV
+    partial of those rows.  Heads and rows are independent, so the rate carries over."""
+    from oracle import attn as oattn
+    G = wl.hq // wl.hkv
+    stride = max(1, len(rows) // budget_rows)
+    sample = np.ascontiguousarray(rows[::stride])
+    qs, dos = np.ascontiguousarray(q[:, :G]), np.ascontiguousarray(do[:, :G])
+    ks, vs = np.ascontiguousarray(k[:, :1]), np.ascontiguousarray(v[:, :1])
+    cu = wl.cu_seqlens
+    seq_of = np.searchsorted(cu, sample, side="right") - 1
+    pairs = int((sample - cu[seq_of] + 1).sum())
+    t0 = time.perf_counter()
+    O, LSE = oattn.attn_fwd(qs, ks, vs, cu, wl.softmax_scale, sample)
+    oattn.attn_dq(qs, ks, vs, dos, cu, wl.softmax_scale, sample, O, LSE)
+    oattn.attn_dkv(qs, ks, vs, dos, cu, wl.softmax_scale, sample, O, LSE)
+    dt = time.perf_counter() - t0
+    flops = 14.0 * pairs * wl.head_dim * G
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oattn.num_threads(), "kind": "oracle",
+            "sample": f"{len(sample)} of the rank's {len(rows)} rows (every {stride}th), {G} query heads + 1 KV head, "
+                      f"fwd + dQ + dK/dV partial, {pairs} pairs, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, help="index into the five workloads (default: 32K packed)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the ring steps of a CP group are simulated locally with all "
+              "KV resident); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import fcp_synth as synth
+    from paper_2602_21788_amd.rank import RankAttention
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    wl = synth.make_workload(args.workload)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
+    ra.set_inputs(q, k, v, do)
+    pairs = ra.pairs()
+    flops_fwd = 4.0 * pairs * wl.head_dim * wl.hq
+    flops_bwd = 10.0 * pairs * wl.head_dim * wl.hq
+
+    names = ["fwd_step", "merge", "zero", "delta", "bwd_step", "finalize"]
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        mark(0); ra.forward_steps()
+        mark(1); ra.merge()
+        mark(2); ra.zero_grads()
+        mark(3); ra.backward_delta()
+        mark(4); ra.backward_steps()
+        mark(5); ra.finalize()
+        mark(6)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    seg_ms = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
+              for i, n in enumerate(names)}
+
+    import paper_2602_21788_amd as fcp
+    assert fcp.fcp_scratch_status(ra.scratch_f)[1] == 0 and fcp.fcp_scratch_status(ra.scratch_b)[1] == 0
+
+    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
+    bwd_tflops = flops_bwd / (seg_ms["bwd_step"] * 1e-3) / 1e12
+    fwd_tflops = flops_fwd / (seg_ms["fwd_step"] * 1e-3) / 1e12
+    merge_gbs = ra.merge_bytes() / (seg_ms["merge"] * 1e-3) / 1e9
+    out = {
+        "metric": "rank-local varlen causal attn TFLOP/s fwd+bwd, % of MFMA bf16 peak",
+        "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": wl.name, "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
+                   "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
+                   "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
+                   "seed": wl.seed},
+        "roofline": {"bound": "mfma", "kernel": "bwd_kernel<128> (fcp_attn_bwd_step)", "achieved": bwd_tflops,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": None},
+        "kernels": {
+            "fwd_step": {"ms": seg_ms["fwd_step"], "tflops": fwd_tflops, "frac_mfma_peak": fwd_tflops / PEAK_BF16_TFLOPS},
+            "bwd_step": {"ms": seg_ms["bwd_step"], "tflops": bwd_tflops, "frac_mfma_peak": bwd_tflops / PEAK_BF16_TFLOPS},
+            "merge": {"ms": seg_ms["merge"], "gbs": merge_gbs, "frac_hbm_peak": merge_gbs / PEAK_HBM_GBS},
+            "delta": {"ms": seg_ms["delta"]}, "zero": {"ms": seg_ms["zero"]}, "finalize": {"ms": seg_ms["finalize"]},
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, do, ra.rows)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
