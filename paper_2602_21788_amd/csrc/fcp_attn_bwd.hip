@@ -5,21 +5,24 @@
 // probabilities of a step are recomputed exactly, P = exp(scale s - LSE), so each step adds
 // its own share:  dV += P^T dO,  dS = P o (dO V^T - delta),  dQ += scale dS K,  dK += scale dS^T Q.
 //
-// gfx950 design
-//   * persistent 256-thread blocks pull (key tile, head) units, longest first;
-//   * a unit = 128 keys of one segment of one work item for one query head; wave w owns keys
-//     32w..32w+31: their K and V fragments live in registers for the whole unit and so do the
-//     fp32 accumulators dK^T, dV^T [channel x own key];
-//   * the loop runs over 32-row query blocks that can see the tile; Q and dO blocks are staged
-//     in LDS (double buffered, next block's global loads in flight during compute);
-//   * S = Q K^T and dP = dO V^T are produced as [query x key] with the key on the lane, so
-//     P and dS are directly the B operands of dV^T += dO^T P and dK^T += Q^T dS, whose A
-//     operands (dO^T, Q^T) come from the row-major LDS tiles by transpose reads;
-//   * dQ needs the contraction over keys: dS goes once through LDS, then wave w computes the
-//     [32 rows x 32 channels] slice w of dS K with K^T fragments kept in registers, and adds it
-//     to the fp32 accumulator with 128-byte-contiguous hardware atomics;
-//   * dK/dV are added to the pool accumulators once per unit (fp32 atomics), which also sums
-//     the query heads of a KV head and the ring steps.
+// gfx950 design: two persistent kernels, because fp32 atomics retire at about one element
+// per L2 channel per clock on this chip (~270 G/s), far too few to accumulate dQ per key tile.
+//
+//   dkv_kernel  unit = 128 keys of one segment of one work item x one KV head.  Wave w owns keys
+//               32w..32w+31: their K and V fragments and the fp32 accumulators dK^T, dV^T
+//               [channel x key] stay in registers while the unit loops over the query heads of
+//               the KV head and over the 32-row query blocks that see the tile.  S = Q K^T and
+//               dP = dO V^T come out as [query x key] with the key on the lane, which is exactly
+//               the B-operand layout of dV^T += dO^T P and dK^T += Q^T dS; dO^T / Q^T are
+//               transpose reads of the row-major LDS tiles.
+//   dq_kernel   unit = 128 query rows of one work item x one query head (the forward's shape).
+//               Wave w owns 32 rows, keeps Q and dO fragments in registers, streams K/V tiles
+//               through LDS, forms S^T = K Q^T and dP^T = V dO^T [key x query] so that dS^T is
+//               the B operand of dQ^T += K^T dS^T with K^T from transpose reads.
+//
+// Both add their result to the caller's fp32 accumulators once per unit: with plain
+// load-add-store when the scheduler found that no other item of the launch touches the same
+// rows (always the case for degree-1 sequences), otherwise with fp32 atomics.
 #include "fcp_internal.h"
 
 namespace fcp {
@@ -41,8 +44,8 @@ struct BwdParams {
   const float* delta;
   const int32_t* cu;
   const fcp_work_desc* work;
-  const SchedHeader* hdr_ro;
-  SchedHeader* hdr;
+  SchedHeader* hdr;          // schedule region of this kernel
+  const int32_t* flags;
   const Tile* tiles;
   float* dq;
   float* dk;
@@ -53,35 +56,40 @@ struct BwdParams {
 
 constexpr float kLog2e = 1.4426950408889634f;
 
-template <int D>
-struct BwdCfg {
-  static constexpr int BN = kBwdBN;                // 128 keys per unit
-  static constexpr int BM = kBwdBM;                // 32 query rows per inner step
-  static constexpr int RSTRIDE = D * 2 + 64;       // Q/dO/K rows in LDS (bytes): serves b128 row reads
-                                                   // (stride = 64 mod 256) and 4-row transpose reads
-  static constexpr int KBYTES = BN * RSTRIDE;      // staged K tile (for the K^T fragments of dQ)
-  static constexpr int QBYTES = BM * RSTRIDE;      // one Q or dO block
-  static constexpr int SSTRIDE = BN * 2 + 16;      // dS rows [query][key] bf16
-  static constexpr int SBYTES = BM * SSTRIDE;
-  static constexpr int STAT_BYTES = 2 * BM * 4;    // LSE (log2 units) and delta of the block
-  static constexpr int STAGE = 2 * QBYTES + STAT_BYTES;
-  static constexpr int OFF_STAGE = KBYTES;
-  static constexpr int OFF_DS = KBYTES + 2 * STAGE;
-  static constexpr int LDS_BYTES = OFF_DS + SBYTES;
-  static constexpr int CPR = D * 2 / 16;           // 16-byte pieces per row
-  static constexpr int QPT = BM * CPR / 256;       // pieces per thread per tensor (2 for D=128, 1 for D=64)
-};
-
-__device__ inline bf16x8 tr_read_8(const unsigned char* p0, int row_stride4) {
-  // two 4-row transpose reads -> 8 k-slots; rows p0 + [0,4) and p0 + row_stride4 bytes + [0,4)
+__device__ inline bf16x8 tr_read_8(const unsigned char* p0, int second_off) {
+  // two 4-row LDS transpose reads -> the 8 k-slots of one MFMA operand
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0 + row_stride4));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0 + second_off));
   return __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+__device__ inline f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) z[i] = 0.f;
+  return z;
+}
+
+// ============================================================================================
+// dK / dV
+// ============================================================================================
 template <int D>
-__global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
-  using C = BwdCfg<D>;
+struct DkvCfg {
+  static constexpr int BN = kBwdBN;                // 128 keys per unit
+  static constexpr int BM = kBwdBM;                // 32 query rows per inner step
+  static constexpr int RSTRIDE = D * 2 + 32;       // Q/dO rows in LDS: compromise between b128 row reads
+                                                   // and 4-row transpose reads (measured)
+  static constexpr int QBYTES = BM * RSTRIDE;
+  static constexpr int STAT_BYTES = 2 * BM * 4;    // LSE (log2 units) and delta of the block
+  static constexpr int STAGE = 2 * QBYTES + STAT_BYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int CPR = D * 2 / 16;           // 16-byte pieces per row
+  static constexpr int QPT = BM * CPR / 256;       // pieces per thread per tensor
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 1) void dkv_kernel(const BwdParams p) {
+  using C = DkvCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   __shared__ int32_t s_unit;
 
@@ -89,13 +97,10 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
   const int lane = tid & 63, wave = tid >> 6;
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = p.hq / p.hkv;
-  const bool per_xcd = (p.hq % kNumXcd) == 0;
+  const bool per_xcd = (p.hkv % kNumXcd) == 0;
   const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
-  const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
-  const int n_units = p.hdr_ro->n_tiles * heads_here;
-
-  // transpose-read lane geometry (see ds_read_b64_tr_b16): inside a 16-lane block the lane
-  // addresses row (l%16)/4, 4 channels at 4*(l%4); blocks alternate channel halves, g2 picks rows
+  const int kvh_here = per_xcd ? p.hkv / kNumXcd : p.hkv;
+  const int n_units = p.hdr->n_tiles * kvh_here;
   const int tr_row = (lane & 15) >> 2;
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
@@ -105,41 +110,29 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
     const int unit = __builtin_amdgcn_readfirstlane(s_unit);
     __syncthreads();
     if (unit >= n_units) break;
-    const int tile_i = unit / heads_here;
-    const int head = xcd * heads_here + unit % heads_here;
-    const int kvh = head / G;
+    const int tile_i = unit / kvh_here;
+    const int kvh = xcd * kvh_here + unit % kvh_here;
     const Tile tile = p.tiles[tile_i];
     const fcp_work_desc w = p.work[tile.work];
     const int seg = tile.idx >> 24, kt = tile.idx & 0xffffff;
+    const bool exclusive = (p.flags[tile.work] & (seg ? kFlagSeg1Exclusive : kFlagSeg0Exclusive)) != 0;
 
-    // keys of the unit
-    const int vis_len = max(0, min(w.k_len[seg], w.q_seq_start + w.q_len - 1 - w.k_seq_start[seg] + 1));
-    const int key0 = kt * C::BN;                               // first key (index in the segment)
+    const int vis_len = max(0, min(w.k_len[seg], w.q_seq_start + w.q_len - w.k_seq_start[seg]));
+    const int key0 = kt * C::BN;
     const int n_keys = min(C::BN, vis_len - key0);             // >= 1 by construction
     const int k_pos0 = w.k_seq_start[seg] + key0;
     const int64_t kv_row0 = (int64_t)p.cu[w.seq] + w.k_seq_start[seg] + key0;
-    const int my_key = 32 * wave + l32;                        // key column this lane owns
+    const int my_key = 32 * wave + l32;
     const int my_key_ld = min(my_key, n_keys - 1);
     const int my_k_pos = k_pos0 + my_key;
     const bool my_key_valid = my_key < n_keys;
 
-    // query blocks that can see the tile
     const int first_row = max(0, k_pos0 - w.q_seq_start);
     const int qb0 = first_row / C::BM;
-    const int qb1 = (w.q_len + C::BM - 1) / C::BM;
+    const int nqb = (w.q_len + C::BM - 1) / C::BM - qb0;       // query blocks per head, >= 1
+    const int n_iter = nqb * G;
 
-    // ---- one-time: K tile -> LDS (for K^T fragments), own-key K and V fragments -> registers
-    {
-      constexpr int PIECES = C::BN * C::CPR;
-#pragma unroll
-      for (int c = 0; c < PIECES / 256; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        const int key = min(r, n_keys - 1);
-        const u32x4 x = *reinterpret_cast<const u32x4*>(p.k + ((kv_row0 + key) * p.hkv + kvh) * D + col * 8);
-        *reinterpret_cast<u32x4*>(smem + r * C::RSTRIDE + col * 16) = x;
-      }
-    }
+    // own-key fragments: B operands of S = Q K^T and dP = dO V^T (lane = key column)
     bf16x8 kf[D / 16], vf[D / 16];
     {
       const int64_t off = ((kv_row0 + my_key_ld) * p.hkv + kvh) * D + 8 * g2;
@@ -150,10 +143,11 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
       }
     }
 
-    // ---- Q / dO block staging -------------------------------------------------------------
     u32x4 qreg[C::QPT], doreg[C::QPT];
     float statreg = 0.f;
-    auto issue_loads = [&](int qb) {
+    auto issue_loads = [&](int it) {
+      const int head = kvh * G + it / nqb;
+      const int qb = qb0 + it % nqb;
 #pragma unroll
       for (int c = 0; c < C::QPT; ++c) {
         const int piece = tid + 256 * c;
@@ -176,7 +170,7 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
       }
     };
     auto store_stage = [&](int buf) {
-      unsigned char* qs = smem + C::OFF_STAGE + buf * C::STAGE;
+      unsigned char* qs = smem + buf * C::STAGE;
       unsigned char* dos = qs + C::QBYTES;
 #pragma unroll
       for (int c = 0; c < C::QPT; ++c) {
@@ -188,49 +182,30 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
       if (tid < 2 * C::BM) reinterpret_cast<float*>(dos + C::QBYTES)[tid] = statreg;
     };
 
-    if (qb0 < qb1) {
-      issue_loads(qb0);
-      store_stage(0);
-    }
+    issue_loads(0);
+    store_stage(0);
     __syncthreads();
-
-    // K^T fragments of this wave's channel slice for dQ = dS K: B operand, lane = channel
-    // 32*wave + l32, k-slots = keys 16*ks + 8*g2 + [0,8)
-    bf16x8 ktf[C::BN / 16];
-    if (wave < D / 32) {
-#pragma unroll
-      for (int ks = 0; ks < C::BN / 16; ++ks) {
-        const unsigned char* a0 = smem + (16 * ks + 8 * g2 + tr_row) * C::RSTRIDE + (32 * wave + tr_col) * 2;
-        ktf[ks] = tr_read_8(a0, 4 * C::RSTRIDE);
-      }
-    }
 
     f32x16 dvacc[D / 32], dkacc[D / 32];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { dvacc[db][i] = 0.f; dkacc[db][i] = 0.f; }
+    for (int db = 0; db < D / 32; ++db) { dvacc[db] = zero16(); dkacc[db] = zero16(); }
 
-    for (int qb = qb0; qb < qb1; ++qb) {
-      const int buf = (qb - qb0) & 1;
-      if (qb + 1 < qb1) issue_loads(qb + 1);
-      const unsigned char* qs = smem + C::OFF_STAGE + buf * C::STAGE;
+    for (int it = 0; it < n_iter; ++it) {
+      const int buf = it & 1;
+      if (it + 1 < n_iter) issue_loads(it + 1);
+      const unsigned char* qs = smem + buf * C::STAGE;
       const unsigned char* dos = qs + C::QBYTES;
       const float* stat = reinterpret_cast<const float*>(dos + C::QBYTES);
-      unsigned char* dsm = smem + C::OFF_DS;
 
+      const int qb = qb0 + it % nqb;
       const int row0 = qb * C::BM;
       const int q_pos0 = w.q_seq_start + row0;
       const int rows_here = min(C::BM, w.q_len - row0);
-      // wave-uniform visibility of this wave's 32 keys from this query block
       const bool wave_sees = (32 * wave < n_keys) && (k_pos0 + 32 * wave <= q_pos0 + rows_here - 1);
       const bool need_mask = (k_pos0 + 32 * wave + 31 > q_pos0) || (32 * wave + 32 > n_keys) || (rows_here < C::BM);
 
       if (wave_sees) {
-        // ---- S = Q K^T, dP = dO V^T   [32 rows x 32 own keys] -------------------------------
-        f32x16 sacc, dpacc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) { sacc[i] = 0.f; dpacc[i] = 0.f; }
+        f32x16 sacc = zero16(), dpacc = zero16();
         const unsigned char* qrow = qs + l32 * C::RSTRIDE + 16 * g2;
         const unsigned char* dorow = dos + l32 * C::RSTRIDE + 16 * g2;
 #pragma unroll
@@ -240,7 +215,7 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
           const bf16x8 ado = *reinterpret_cast<const bf16x8*>(dorow + 32 * ks);
           dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ado, vf[ks], dpacc, 0, 0, 0);
         }
-        // ---- P = exp2(s c - LSE2), dS = P (dP - delta); register i is row 8*(i/4) + 4*g2 + i%4
+        // register i is query row 8*(i/4) + 4*g2 + i%4 of the block
         bf16x8 pb[2], dsb[2];
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
@@ -252,14 +227,10 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
             const int r = 8 * r4 + 4 * g2 + e;
             float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, -lse4[e]));
             if (need_mask && (!my_key_valid || r >= rows_here || my_k_pos > q_pos0 + r)) pr = 0.f;
-            const float ds = pr * (dpacc[i] - del4[e]);
             pb[i / 8][i % 8] = (__bf16)pr;
-            dsb[i / 8][i % 8] = (__bf16)ds;
-            // dS to LDS as [row][key] for the dQ contraction
-            *reinterpret_cast<__bf16*>(dsm + r * C::SSTRIDE + my_key * 2) = (__bf16)ds;
+            dsb[i / 8][i % 8] = (__bf16)(pr * (dpacc[i] - del4[e]));
           }
         }
-        // ---- dV^T += dO^T P,  dK^T += Q^T dS  [channel x own key] ----------------------------
         // k-slots of step t are rows 16t + 4*g2 + [0,4) and 16t + 8 + 4*g2 + [0,4), matching pb/dsb
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -272,49 +243,249 @@ __global__ __launch_bounds__(256, 1) void bwd_kernel(const BwdParams p) {
             dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_q, dsb[t], dkacc[db], 0, 0, 0);
           }
         }
-      } else {
-        // keys of this wave are invisible to the block: their dS columns are zero
-#pragma unroll
-        for (int r = 0; r < 16; ++r)
-          *reinterpret_cast<__bf16*>(dsm + (r + 16 * g2) * C::SSTRIDE + my_key * 2) = (__bf16)0.f;
       }
-      __syncthreads();   // dS complete
-
-      // ---- dQ slice: [32 rows x channels 32*wave..+31] = dS [32 x 128] K [128 x slice] -------
-      if (wave < D / 32) {
-        f32x16 dqacc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) dqacc[i] = 0.f;
-        const unsigned char* dsrow = dsm + l32 * C::SSTRIDE + 16 * g2;
-#pragma unroll
-        for (int ks = 0; ks < C::BN / 16; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(dsrow + 32 * ks);
-          dqacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, ktf[ks], dqacc, 0, 0, 0);
-        }
-        float* dqp = p.dq + ((int64_t)(w.q_local_off + row0) * p.hq + head) * D + 32 * wave + l32;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int r = 8 * (i / 4) + 4 * g2 + (i % 4);
-          if (r < rows_here) unsafeAtomicAdd(dqp + (int64_t)r * p.hq * D, dqacc[i] * p.scale);
-        }
-      }
-      if (qb + 1 < qb1) store_stage(buf ^ 1);
-      __syncthreads();   // next stage visible; dS free for reuse
+      if (it + 1 < n_iter) store_stage(buf ^ 1);
+      __syncthreads();
     }
 
-    // ---- epilogue: dK^T, dV^T [channel x own key] -> pool accumulators -------------------------
+    // epilogue: dK^T, dV^T [channel x own key] -> pool accumulators
     if (my_key_valid) {
-      const int64_t off = ((kv_row0 + my_key) * p.hkv + kvh) * D;
+      float* dvp = p.dv + ((kv_row0 + my_key) * p.hkv + kvh) * D + 4 * g2;
+      float* dkp = p.dk + ((kv_row0 + my_key) * p.hkv + kvh) * D + 4 * g2;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int c = 32 * db + 8 * (i / 4) + 4 * g2 + (i % 4);
-          unsafeAtomicAdd(p.dv + off + c, dvacc[db][i]);
-          unsafeAtomicAdd(p.dk + off + c, dkacc[db][i] * p.scale);
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int c = 32 * db + 8 * r4;
+          if (exclusive) {
+            f32x4 a = *reinterpret_cast<f32x4*>(dvp + c), b = *reinterpret_cast<f32x4*>(dkp + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { a[e] += dvacc[db][4 * r4 + e]; b[e] += dkacc[db][4 * r4 + e] * p.scale; }
+            *reinterpret_cast<f32x4*>(dvp + c) = a;
+            *reinterpret_cast<f32x4*>(dkp + c) = b;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              unsafeAtomicAdd(dvp + c + e, dvacc[db][4 * r4 + e]);
+              unsafeAtomicAdd(dkp + c + e, dkacc[db][4 * r4 + e] * p.scale);
+            }
+          }
         }
     }
   }
+}
+
+// ============================================================================================
+// dQ
+// ============================================================================================
+template <int D>
+struct DqCfg {
+  static constexpr int BM = kFwdBM;               // 128 query rows per unit (32 per wave)
+  static constexpr int BN = kFwdBN;               // 64 keys per LDS tile
+  static constexpr int KSTRIDE = D * 2 + 32;      // K rows: b128 row reads AND transpose reads
+  static constexpr int VSTRIDE = D * 2 + 16;      // V rows: b128 row reads only
+  static constexpr int KBYTES = BN * KSTRIDE;
+  static constexpr int VBYTES = BN * VSTRIDE;
+  static constexpr int STAGE = KBYTES + VBYTES;
+  static constexpr int LDS_BYTES = 2 * STAGE;
+  static constexpr int CHUNKS = BN * D * 2 / 16;
+  static constexpr int CPT = CHUNKS / 256;
+  static constexpr int CPR = D * 2 / 16;
+};
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void dq_kernel(const BwdParams p) {
+  using C = DqCfg<D>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  __shared__ int32_t s_unit;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, g2 = lane >> 5;
+  const int G = p.hq / p.hkv;
+  const bool per_xcd = (p.hq % kNumXcd) == 0;
+  const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
+  const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
+  const int n_units = p.hdr->n_tiles * heads_here;
+
+  for (;;) {
+    if (tid == 0) s_unit = atomicAdd(&p.hdr->counter[xcd], 1);
+    __syncthreads();
+    const int unit = __builtin_amdgcn_readfirstlane(s_unit);
+    __syncthreads();
+    if (unit >= n_units) break;
+    const int tile_i = unit / heads_here;
+    const int head = xcd * heads_here + unit % heads_here;
+    const int kvh = head / G;
+    const Tile tile = p.tiles[tile_i];
+    const fcp_work_desc w = p.work[tile.work];
+    const bool exclusive = (p.flags[tile.work] & kFlagQExclusive) != 0;
+
+    const int q_r0 = tile.idx * C::BM;
+    const int rows_here = min(C::BM, w.q_len - q_r0);
+    const int wave_r0 = q_r0 + wave * 32;
+    const bool wave_active = wave * 32 < rows_here;
+    const int my_row = wave_r0 + l32;
+    const bool row_valid = my_row < w.q_len;
+    const int row_ld = min(my_row, w.q_len - 1);
+    const int q_pos = w.q_seq_start + my_row;
+    const int wave_first_pos = w.q_seq_start + wave_r0;
+    const int wave_last_pos = w.q_seq_start + min(wave_r0 + 31, w.q_len - 1);
+
+    // Q and dO fragments: B operands (lane = query column), channels 16*ks + 8*g2 + [0,8)
+    bf16x8 qf[D / 16], dof[D / 16];
+    {
+      const int64_t off = ((int64_t)(w.q_local_off + row_ld) * p.hq + head) * D + 8 * g2;
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
+        dof[ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
+      }
+    }
+    float lse2, delta;
+    {
+      const int64_t off = (int64_t)head * p.tq + w.q_local_off + row_ld;
+      const float l = p.lse[off];
+      lse2 = l == -INFINITY ? INFINITY : l * kLog2e;
+      delta = p.delta[off];
+    }
+
+    const int last_pos = w.q_seq_start + q_r0 + rows_here - 1;
+    int vis[2], nt[2];
+    int64_t kv_row0[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      int vl = 0;
+      if (s < w.n_seg) vl = max(0, min(w.k_len[s], last_pos - w.k_seq_start[s] + 1));
+      vis[s] = vl;
+      nt[s] = (vl + C::BN - 1) / C::BN;
+      kv_row0[s] = (int64_t)p.cu[w.seq] + w.k_seq_start[s];
+    }
+    const int n_iter = nt[0] + nt[1];
+
+    f32x16 dqacc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) dqacc[db] = zero16();
+
+    u32x4 kreg[C::CPT], vreg[C::CPT];
+    auto issue_loads = [&](int it) {
+      const int s = it >= nt[0] ? 1 : 0;
+      const int kt = it - (s ? nt[0] : 0);
+      const int vl = vis[s];
+#pragma unroll
+      for (int c = 0; c < C::CPT; ++c) {
+        const int piece = tid + 256 * c;
+        const int r = piece / C::CPR, col = piece % C::CPR;
+        const int key = min(kt * C::BN + r, vl - 1);
+        const int64_t off = ((kv_row0[s] + key) * p.hkv + kvh) * D + col * 8;
+        kreg[c] = *reinterpret_cast<const u32x4*>(p.k + off);
+        vreg[c] = *reinterpret_cast<const u32x4*>(p.v + off);
+      }
+    };
+    auto store_tile = [&](int buf) {
+      unsigned char* kb = smem + buf * C::STAGE;
+      unsigned char* vb = kb + C::KBYTES;
+#pragma unroll
+      for (int c = 0; c < C::CPT; ++c) {
+        const int piece = tid + 256 * c;
+        const int r = piece / C::CPR, col = piece % C::CPR;
+        *reinterpret_cast<u32x4*>(kb + r * C::KSTRIDE + col * 16) = kreg[c];
+        *reinterpret_cast<u32x4*>(vb + r * C::VSTRIDE + col * 16) = vreg[c];
+      }
+    };
+
+    if (n_iter > 0) {
+      issue_loads(0);
+      store_tile(0);
+    }
+    __syncthreads();
+
+    for (int it = 0; it < n_iter; ++it) {
+      const int buf = it & 1;
+      if (it + 1 < n_iter) issue_loads(it + 1);
+      const int s = it >= nt[0] ? 1 : 0;
+      const int kt = it - (s ? nt[0] : 0);
+      const int k_pos0 = w.k_seq_start[s] + kt * C::BN;
+      const int n_valid = min(C::BN, vis[s] - kt * C::BN);
+      const bool wave_sees = wave_active && k_pos0 <= wave_last_pos;
+      const bool need_mask = (k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN);
+
+      if (wave_sees) {
+        const unsigned char* kb = smem + buf * C::STAGE;
+        const unsigned char* vb = kb + C::KBYTES;
+        // S^T = K Q^T and dP^T = V dO^T   [key x query], two 32-key blocks
+        f32x16 sacc[2], dpacc[2];
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk) {
+          sacc[kbk] = zero16();
+          dpacc[kbk] = zero16();
+          const unsigned char* krow = kb + (32 * kbk + l32) * C::KSTRIDE + 16 * g2;
+          const unsigned char* vrow = vb + (32 * kbk + l32) * C::VSTRIDE + 16 * g2;
+#pragma unroll
+          for (int ks = 0; ks < D / 16; ++ks) {
+            const bf16x8 ak = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
+            sacc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qf[ks], sacc[kbk], 0, 0, 0);
+            const bf16x8 av = *reinterpret_cast<const bf16x8*>(vrow + 32 * ks);
+            dpacc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[ks], dpacc[kbk], 0, 0, 0);
+          }
+        }
+        // dS^T = P^T o (dP^T - delta); register i of block kbk is key 32*kbk + 8*(i/4) + 4*g2 + i%4
+        bf16x8 dsf[4];
+#pragma unroll
+        for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            float pr = __builtin_amdgcn_exp2f(fmaf(sacc[kbk][i], p.scale_log2, -lse2));
+            if (need_mask) {
+              const int kk = 32 * kbk + 8 * (i / 4) + 4 * g2 + (i % 4);
+              if (kk >= n_valid || k_pos0 + kk > q_pos) pr = 0.f;
+            }
+            dsf[2 * kbk + i / 8][i % 8] = (__bf16)(pr * (dpacc[kbk][i] - delta));
+          }
+        // dQ^T[channel, query] += K^T dS^T; A operand by transpose reads of the K tile
+        const unsigned char* kbase = kb + (4 * g2 + ((lane & 15) >> 2)) * C::KSTRIDE +
+                                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            const bf16x8 a = tr_read_8(kbase + (16 * t) * C::KSTRIDE + 64 * db, 8 * C::KSTRIDE);
+            dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[t], dqacc[db], 0, 0, 0);
+          }
+      }
+      if (it + 1 < n_iter) store_tile(buf ^ 1);
+      __syncthreads();
+    }
+
+    // epilogue: dQ^T [channel x query] * scale -> accumulator rows
+    if (row_valid) {
+      float* dqp = p.dq + ((int64_t)(w.q_local_off + my_row) * p.hq + head) * D + 4 * g2;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int c = 32 * db + 8 * r4;
+          if (exclusive) {
+            f32x4 a = *reinterpret_cast<f32x4*>(dqp + c);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[e] += dqacc[db][4 * r4 + e] * p.scale;
+            *reinterpret_cast<f32x4*>(dqp + c) = a;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dqp + c + e, dqacc[db][4 * r4 + e] * p.scale);
+          }
+        }
+    }
+  }
+}
+
+template <typename K>
+int set_lds_once(K kernel, int bytes, bool* done) {
+  if (!*done) {
+    FCP_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    *done = true;
+  }
+  return FCP_OK;
 }
 
 }  // namespace
@@ -338,24 +509,29 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   if (head_dim != 64 && head_dim != 128) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: head_dim %d not 64/128", head_dim);
   if (!(softmax_scale > 0.f) || !(softmax_scale < 1e30f)) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: softmax_scale must be positive and finite");
   const uintptr_t align_mask = reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
-                               reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(d_o);
-  if (align_mask & 15u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: q/k/v/d_o must be 16-byte aligned");
-  if (reinterpret_cast<uintptr_t>(scratch) & 63u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: scratch must be 64-byte aligned");
+                               reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(d_o) |
+                               reinterpret_cast<uintptr_t>(dq_acc) | reinterpret_cast<uintptr_t>(dk_acc) |
+                               reinterpret_cast<uintptr_t>(dv_acc);
+  if (align_mask & 15u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: tensors must be 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(scratch) & 255u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: scratch must be 256-byte aligned");
   const size_t need = fcp_scratch_bytes(FCP_SCRATCH_BWD, tq, tkv, hq, hkv, head_dim, n_work, 1);
   if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_bwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
 
   hipStream_t st = (hipStream_t)stream;
-  const int64_t cap = fcp::bwd_tile_cap(tkv, n_work);
-  if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: too many tiles");
-  int rc = fcp::launch_schedule(true, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap, scratch, nullptr, 0, st);
+  const int64_t cap_kv = fcp::kv_tile_cap(tkv, n_work);
+  const int64_t cap_q = fcp::q_tile_cap(tq, tkv, n_work, 1 << 20);
+  if (cap_kv > INT32_MAX / 64 || cap_q > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: too many tiles");
+  void* region_kv = scratch;
+  void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
+  int rc = fcp::launch_schedule(true, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
+  if (rc != FCP_OK) return rc;
+  rc = fcp::launch_schedule(false, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
 
   fcp::BwdParams p;
   p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v; p.d_o = (const uint16_t*)d_o;
   p.lse = lse; p.delta = delta; p.cu = cu_seqlens_kv; p.work = work;
-  p.hdr_ro = fcp::sched_header(scratch); p.hdr = (fcp::SchedHeader*)scratch;
-  p.tiles = fcp::sched_tiles(scratch, n_work);
   p.dq = dq_acc; p.dk = dk_acc; p.dv = dv_acc;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.scale = softmax_scale; p.scale_log2 = softmax_scale * fcp::kLog2e;
@@ -363,26 +539,40 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   int dev = 0, n_cu = 256;
   FCP_HIP_CHECK(hipGetDevice(&dev));
   FCP_HIP_CHECK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  int64_t units = cap * hq;
-  int64_t blocks = (int64_t)n_cu;
-  if (blocks > units) blocks = (units + 7) / 8 * 8;
-  if (blocks < 8) blocks = 8;
+  auto grid_for = [&](int64_t units, int per_cu) {
+    int64_t blocks = (int64_t)n_cu * per_cu;
+    if (blocks > units) blocks = (units + 7) / 8 * 8;   // a multiple of the XCD count
+    if (blocks < 8) blocks = 8;
+    return dim3((unsigned)blocks);
+  };
+
+  // dK/dV over key tiles
+  p.hdr = (fcp::SchedHeader*)region_kv;
+  p.flags = fcp::sched_flags(region_kv, n_work);
+  p.tiles = fcp::sched_tiles(region_kv, n_work);
   if (head_dim == 128) {
-    static bool attr_done = false;
-    if (!attr_done) {
-      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::bwd_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        fcp::BwdCfg<128>::LDS_BYTES));
-      attr_done = true;
-    }
-    hipLaunchKernelGGL(fcp::bwd_kernel<128>, dim3((unsigned)blocks), dim3(256), fcp::BwdCfg<128>::LDS_BYTES, st, p);
+    static bool done = false;
+    if ((rc = fcp::set_lds_once(fcp::dkv_kernel<128>, fcp::DkvCfg<128>::LDS_BYTES, &done)) != FCP_OK) return rc;
+    hipLaunchKernelGGL(fcp::dkv_kernel<128>, grid_for(cap_kv * hkv, 1), dim3(256), fcp::DkvCfg<128>::LDS_BYTES, st, p);
   } else {
-    static bool attr_done = false;
-    if (!attr_done) {
-      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::bwd_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        fcp::BwdCfg<64>::LDS_BYTES));
-      attr_done = true;
-    }
-    hipLaunchKernelGGL(fcp::bwd_kernel<64>, dim3((unsigned)blocks), dim3(256), fcp::BwdCfg<64>::LDS_BYTES, st, p);
+    static bool done = false;
+    if ((rc = fcp::set_lds_once(fcp::dkv_kernel<64>, fcp::DkvCfg<64>::LDS_BYTES, &done)) != FCP_OK) return rc;
+    hipLaunchKernelGGL(fcp::dkv_kernel<64>, grid_for(cap_kv * hkv, 1), dim3(256), fcp::DkvCfg<64>::LDS_BYTES, st, p);
+  }
+  FCP_HIP_CHECK(hipGetLastError());
+
+  // dQ over query tiles
+  p.hdr = (fcp::SchedHeader*)region_q;
+  p.flags = fcp::sched_flags(region_q, n_work);
+  p.tiles = fcp::sched_tiles(region_q, n_work);
+  if (head_dim == 128) {
+    static bool done = false;
+    if ((rc = fcp::set_lds_once(fcp::dq_kernel<128>, fcp::DqCfg<128>::LDS_BYTES, &done)) != FCP_OK) return rc;
+    hipLaunchKernelGGL(fcp::dq_kernel<128>, grid_for(cap_q * hq, 2), dim3(256), fcp::DqCfg<128>::LDS_BYTES, st, p);
+  } else {
+    static bool done = false;
+    if ((rc = fcp::set_lds_once(fcp::dq_kernel<64>, fcp::DqCfg<64>::LDS_BYTES, &done)) != FCP_OK) return rc;
+    hipLaunchKernelGGL(fcp::dq_kernel<64>, grid_for(cap_q * hq, 2), dim3(256), fcp::DqCfg<64>::LDS_BYTES, st, p);
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;

@@ -323,7 +323,7 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
     return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: partial output too large");
 
   hipStream_t st = (hipStream_t)stream;
-  const int64_t cap = fcp::fwd_tile_cap(tq, n_work, n_parts);
+  const int64_t cap = fcp::q_tile_cap(tq, tkv, n_work, n_parts);
   if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
   int rc = fcp::launch_schedule(false, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
                                 lse_part, (int64_t)n_parts * hq * tq, st);

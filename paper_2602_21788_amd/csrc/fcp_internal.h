@@ -42,21 +42,40 @@ constexpr int kFwdBN = 64;       // keys per forward inner step
 constexpr int kBwdBN = 128;      // keys per backward tile
 constexpr int kBwdBM = 32;       // query rows per backward inner step
 
-int64_t fwd_tile_cap(int32_t tq, int64_t n_work, int32_t n_parts);
-int64_t bwd_tile_cap(int32_t tkv, int64_t n_work);
+// Upper bounds on the number of tiles of a valid plan (anything beyond is dropped and
+// counted as rejected).  Query tiles: every (row, slot) belongs to at most one item, and over
+// a rank's items the query chunks of a sequence add up to at most its length.  Key tiles:
+// over a rank's items the key segments of a sequence add up to at most twice its length.
+int64_t q_tile_cap(int32_t tq, int32_t tkv, int64_t n_work, int32_t n_parts);
+int64_t kv_tile_cap(int32_t tkv, int64_t n_work);
 
-// scratch layout: SchedHeader | item offsets int32[n_work+1] (padded to 64 B) | Tile[cap]
-size_t sched_item_off_bytes(int64_t n_work);
-inline const SchedHeader* sched_header(const void* scratch) { return static_cast<const SchedHeader*>(scratch); }
-inline const Tile* sched_tiles(const void* scratch, int64_t n_work) {
-  return reinterpret_cast<const Tile*>(static_cast<const char*>(scratch) + sizeof(SchedHeader) +
-                                       sched_item_off_bytes(n_work));
+// One schedule region: SchedHeader | item offsets int32[n_work+1] | item flags int32[n_work]
+// | Tile[cap]; every part padded to 64 bytes, the region to 256.
+constexpr int32_t kFlagQExclusive = 1;    // no other item of the launch covers these query rows
+constexpr int32_t kFlagSeg0Exclusive = 2; // no other item's key segment overlaps segment 0 / 1
+constexpr int32_t kFlagSeg1Exclusive = 4;
+inline size_t pad_to(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline size_t sched_item_off_bytes(int64_t n_work) { return pad_to((size_t)(n_work + 1) * sizeof(int32_t), 64); }
+inline size_t sched_flags_bytes(int64_t n_work) { return pad_to((size_t)(n_work > 0 ? n_work : 1) * sizeof(int32_t), 64); }
+inline size_t sched_region_bytes(int64_t n_work, int64_t cap) {
+  return pad_to(sizeof(SchedHeader) + sched_item_off_bytes(n_work) + sched_flags_bytes(n_work) +
+                (size_t)cap * sizeof(Tile), 256);
+}
+inline const SchedHeader* sched_header(const void* region) { return static_cast<const SchedHeader*>(region); }
+inline const int32_t* sched_flags(const void* region, int64_t n_work) {
+  return reinterpret_cast<const int32_t*>(static_cast<const char*>(region) + sizeof(SchedHeader) +
+                                          sched_item_off_bytes(n_work));
+}
+inline const Tile* sched_tiles(const void* region, int64_t n_work) {
+  return reinterpret_cast<const Tile*>(static_cast<const char*>(region) + sizeof(SchedHeader) +
+                                       sched_item_off_bytes(n_work) + sched_flags_bytes(n_work));
 }
 
-// Builds the tile list for a launch and (forward) fills lse_part with -inf.
-int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
+// Builds one tile list in `region` (key tiles if `key_tiles`, else query tiles) and, when
+// lse_fill is given, fills it with -inf.
+int launch_schedule(bool key_tiles, const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
-                    int32_t n_parts, int64_t tile_cap, void* scratch, float* lse_fill,
+                    int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
                     int64_t lse_fill_n, hipStream_t stream);
 
 }  // namespace fcp

@@ -18,6 +18,7 @@ namespace {
 
 constexpr int kSchedThreads = 1024;
 constexpr int kBuckets = 2048;
+constexpr int kMaxExclusiveScan = 4096;   // beyond this many items the O(n^2) overlap scan is skipped
 
 struct ItemInfo {
   bool ok;
@@ -29,9 +30,9 @@ struct ItemInfo {
 __device__ inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
 
 __device__ inline bool item_valid(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
-                                  int32_t tq, int32_t tkv, int32_t n_parts, bool backward) {
+                                  int32_t tq, int32_t tkv, int32_t n_parts, bool check_step) {
   if (w.seq < 0 || w.seq >= n_seqs) return false;
-  if (!backward && (w.step < 0 || w.step >= n_parts)) return false;
+  if (check_step && (w.step < 0 || w.step >= n_parts)) return false;
   if (w.q_len < 1 || w.q_local_off < 0 || w.q_seq_start < 0) return false;
   if ((int64_t)w.q_local_off + w.q_len > (int64_t)tq) return false;
   if ((int64_t)w.q_seq_start + w.q_len > (int64_t)(1 << 30)) return false;
@@ -71,9 +72,10 @@ __device__ inline int32_t bwd_cost(const fcp_work_desc& w, int s, int32_t kt) {
 }
 
 __device__ inline ItemInfo item_info(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
-                                     int32_t tq, int32_t tkv, int32_t n_parts, bool backward) {
+                                     int32_t tq, int32_t tkv, int32_t n_parts, bool backward,
+                                     bool check_step) {
   ItemInfo r{false, 0, 0, 0};
-  r.ok = item_valid(w, cu, n_seqs, tq, tkv, n_parts, backward);
+  r.ok = item_valid(w, cu, n_seqs, tq, tkv, n_parts, check_step);
   if (!r.ok) return r;
   if (!backward) {
     r.n_tiles = ceil_div(w.q_len, kFwdBM);
@@ -110,10 +112,10 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32
 }
 
 __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
-    int backward, const fcp_work_desc* __restrict__ work, int32_t n_work,
+    int backward, int check_step, const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
-    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, Tile* tiles, float* lse_fill,
-    int64_t lse_fill_n) {
+    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
+    float* lse_fill, int64_t lse_fill_n) {
   if (blockIdx.x > 0) {  // the other blocks pre-fill the partial LSE with -inf
     const int64_t stride = (int64_t)(gridDim.x - 1) * kSchedThreads;
     for (int64_t i = (int64_t)(blockIdx.x - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
@@ -134,7 +136,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     int32_t cnt = 0;
     if (i < n_work) {
       const fcp_work_desc w = work[i];
-      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0);
+      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0);
       if (!info.ok) atomicAdd(&s_rej, 1);
       cnt = info.n_tiles;
       if (info.max_cost > 0) atomicMax(&s_max, info.max_cost);
@@ -146,6 +148,33 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     __syncthreads();
     if (tid == 0) s_carry = carry + total;
     __syncthreads();
+  }
+  // Exclusivity flags: an item whose query rows (key segments) no other valid item of this
+  // launch touches lets the backward kernels add to dQ (dK/dV) without atomics.
+  for (int32_t i = tid; i < n_work; i += kSchedThreads) {
+    int32_t flags = 0;
+    if (n_work <= kMaxExclusiveScan) {
+      const fcp_work_desc a = work[i];
+      if (item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0)) {
+        flags = kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive;
+        if (a.n_seg == 2 && a.k_seq_start[0] + a.k_len[0] > a.k_seq_start[1]) flags &= kFlagQExclusive;
+        for (int32_t j = 0; j < n_work; ++j) {
+          if (j == i) continue;
+          const fcp_work_desc b = work[j];
+          if (!item_valid(b, cu, n_seqs, tq, tkv, n_parts, check_step != 0)) continue;
+          if (a.q_local_off < b.q_local_off + b.q_len && b.q_local_off < a.q_local_off + a.q_len)
+            flags &= ~kFlagQExclusive;
+          if (a.seq == b.seq) {
+            for (int sa = 0; sa < a.n_seg; ++sa)
+              for (int sb = 0; sb < b.n_seg; ++sb)
+                if (a.k_seq_start[sa] < b.k_seq_start[sb] + b.k_len[sb] &&
+                    b.k_seq_start[sb] < a.k_seq_start[sa] + a.k_len[sa])
+                  flags &= ~(sa == 0 ? kFlagSeg0Exclusive : kFlagSeg1Exclusive);
+          }
+        }
+      }
+    }
+    item_flags[i] = flags;
   }
   const int32_t total_tiles = s_carry;
   const int32_t n_tiles = min(total_tiles, tile_cap);
@@ -213,27 +242,25 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
 
 }  // namespace
 
-int64_t fwd_tile_cap(int32_t tq, int64_t n_work, int32_t n_parts) {
-  return n_work + (int64_t)n_parts * ((tq + kFwdBM - 1) / kFwdBM);
+int64_t q_tile_cap(int32_t tq, int32_t tkv, int64_t n_work, int32_t n_parts) {
+  const int64_t by_slots = (int64_t)n_parts * ((tq + kFwdBM - 1) / kFwdBM);
+  const int64_t by_tokens = (int64_t)((tkv + kFwdBM - 1) / kFwdBM);
+  return n_work + (by_slots < by_tokens ? by_slots : by_tokens);
 }
 
-int64_t bwd_tile_cap(int32_t tkv, int64_t n_work) {
-  // per sequence the key segments of one rank's items add up to at most twice its length
+int64_t kv_tile_cap(int32_t tkv, int64_t n_work) {
   return 2 * n_work + 2 * (int64_t)((tkv + kBwdBN - 1) / kBwdBN);
 }
 
-static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-size_t sched_item_off_bytes(int64_t n_work) { return align_up((size_t)(n_work + 1) * sizeof(int32_t), 64); }
-
 int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
-                    int32_t n_parts, int64_t tile_cap, void* scratch, float* lse_fill,
+                    int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
                     int64_t lse_fill_n, hipStream_t stream) {
-  char* base = static_cast<char*>(scratch);
+  char* base = static_cast<char*>(region);
   SchedHeader* hdr = reinterpret_cast<SchedHeader*>(base);
   int32_t* item_off = reinterpret_cast<int32_t*>(base + sizeof(SchedHeader));
-  Tile* tiles = reinterpret_cast<Tile*>(base + sizeof(SchedHeader) + sched_item_off_bytes(n_work));
+  int32_t* item_flags = const_cast<int32_t*>(sched_flags(region, n_work));
+  Tile* tiles = const_cast<Tile*>(sched_tiles(region, n_work));
   int fill_blocks = 0;
   if (lse_fill && lse_fill_n > 0) {
     fill_blocks = (int)((lse_fill_n + kSchedThreads * 4 - 1) / (kSchedThreads * 4));
@@ -241,8 +268,8 @@ int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
     if (fill_blocks < 1) fill_blocks = 1;
   }
   hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks), dim3(kSchedThreads), 0, stream,
-                     backward ? 1 : 0, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
-                     (int32_t)tile_cap, hdr, item_off, tiles, lse_fill, lse_fill_n);
+                     backward ? 1 : 0, lse_fill ? 1 : 0, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
+                     (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
 }
@@ -253,9 +280,10 @@ extern "C" size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t 
                                     int32_t head_dim, int64_t n_work, int32_t n_parts) {
   (void)hq; (void)hkv; (void)head_dim;
   if (tq < 0 || tkv < 0 || n_work < 0 || n_parts < 0) return 0;
-  const int64_t cap = which == FCP_SCRATCH_BWD ? fcp::bwd_tile_cap(tkv, n_work)
-                                               : fcp::fwd_tile_cap(tq, n_work, n_parts);
-  return sizeof(fcp::SchedHeader) + fcp::sched_item_off_bytes(n_work) + (size_t)cap * sizeof(fcp::Tile) + 256;
+  if (which == FCP_SCRATCH_BWD)   // key-tile list (dK/dV kernel) followed by query-tile list (dQ kernel)
+    return fcp::sched_region_bytes(n_work, fcp::kv_tile_cap(tkv, n_work)) +
+           fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, 1 << 20));
+  return fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, n_parts));
 }
 
 extern "C" int fcp_scratch_status(const void* scratch, void* stream, int32_t* n_tiles, int32_t* n_rejected) {
