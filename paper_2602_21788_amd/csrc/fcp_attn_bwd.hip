@@ -201,10 +201,9 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(const BwdParams p) {
       const int row0 = qb * C::BM;
       const int q_pos0 = w.q_seq_start + row0;
       const int rows_here = min(C::BM, w.q_len - row0);
-      const bool wave_sees = (32 * wave < n_keys) && (k_pos0 + 32 * wave <= q_pos0 + rows_here - 1);
       const bool need_mask = (k_pos0 + 32 * wave + 31 > q_pos0) || (32 * wave + 32 > n_keys) || (rows_here < C::BM);
 
-      if (wave_sees) {
+      {
         f32x16 sacc = zero16(), dpacc = zero16();
         const unsigned char* qrow = qs + l32 * C::RSTRIDE + 16 * g2;
         const unsigned char* dorow = dos + l32 * C::RSTRIDE + 16 * g2;
