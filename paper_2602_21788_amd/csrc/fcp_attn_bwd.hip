@@ -204,44 +204,73 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(const BwdParams p) {
       const bool need_mask = (k_pos0 + 32 * wave + 31 > q_pos0) || (32 * wave + 32 > n_keys) || (rows_here < C::BM);
 
       {
-        f32x16 sacc = zero16(), dpacc = zero16();
+        // Phase 1: all row fragments of the block are requested before the first MFMA, so the
+        // LDS latency is paid once and not once per MFMA.
+        bf16x8 aq[D / 16], ado[D / 16];
         const unsigned char* qrow = qs + l32 * C::RSTRIDE + 16 * g2;
         const unsigned char* dorow = dos + l32 * C::RSTRIDE + 16 * g2;
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks) {
-          const bf16x8 aq = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[ks], sacc, 0, 0, 0);
-          const bf16x8 ado = *reinterpret_cast<const bf16x8*>(dorow + 32 * ks);
-          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ado, vf[ks], dpacc, 0, 0, 0);
+          aq[ks] = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
+          ado[ks] = *reinterpret_cast<const bf16x8*>(dorow + 32 * ks);
         }
-        // register i is query row 8*(i/4) + 4*g2 + i%4 of the block
-        bf16x8 pb[2], dsb[2];
+        __builtin_amdgcn_sched_barrier(0);
+        // Phase 2: S = Q K^T, dP = dO V^T  [32 rows x 32 own keys]
+        f32x16 sacc = zero16(), dpacc = zero16();
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const f32x4 lse4 = *reinterpret_cast<const f32x4*>(stat + 8 * r4 + 4 * g2);
-          const f32x4 del4 = *reinterpret_cast<const f32x4*>(stat + C::BM + 8 * r4 + 4 * g2);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int i = 4 * r4 + e;
-            const int r = 8 * r4 + 4 * g2 + e;
-            float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, -lse4[e]));
-            if (need_mask && (!my_key_valid || r >= rows_here || my_k_pos > q_pos0 + r)) pr = 0.f;
-            pb[i / 8][i % 8] = (__bf16)pr;
-            dsb[i / 8][i % 8] = (__bf16)(pr * (dpacc[i] - del4[e]));
-          }
+        for (int ks = 0; ks < D / 16; ++ks) {
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[ks], kf[ks], sacc, 0, 0, 0);
+          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ado[ks], vf[ks], dpacc, 0, 0, 0);
         }
-        // k-slots of step t are rows 16t + 4*g2 + [0,4) and 16t + 8 + 4*g2 + [0,4), matching pb/dsb
+        // Phase 3: transposed fragments for the second pair of contractions and the row
+        // statistics are requested now; they arrive while the MFMAs above drain and the
+        // exponentials below run.
+        bf16x8 tdo[2][D / 32], tq[2][D / 32];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int db = 0; db < D / 32; ++db) {
             const int roff = (16 * t + 4 * g2 + tr_row) * C::RSTRIDE + (32 * db + tr_col) * 2;
-            const bf16x8 a_do = tr_read_8(dos + roff, 8 * C::RSTRIDE);
-            dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_do, pb[t], dvacc[db], 0, 0, 0);
-            const bf16x8 a_q = tr_read_8(qs + roff, 8 * C::RSTRIDE);
-            dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_q, dsb[t], dkacc[db], 0, 0, 0);
+            tdo[t][db] = tr_read_8(dos + roff, 8 * C::RSTRIDE);
+            tq[t][db] = tr_read_8(qs + roff, 8 * C::RSTRIDE);
+          }
+        f32x4 lse4[4], del4[4];
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          lse4[r4] = *reinterpret_cast<const f32x4*>(stat + 8 * r4 + 4 * g2);
+          del4[r4] = *reinterpret_cast<const f32x4*>(stat + C::BM + 8 * r4 + 4 * g2);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // Phase 4: P = exp2(c s - LSE2), dS = P (dP - delta); register i is query row
+        // 8*(i/4) + 4*g2 + i%4 of the block
+        bf16x8 pb[2], dsb[2];
+        if (need_mask) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int r = 8 * (i / 4) + 4 * g2 + (i % 4);
+            float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, -lse4[i / 4][i % 4]));
+            if (!my_key_valid || r >= rows_here || my_k_pos > q_pos0 + r) pr = 0.f;
+            pb[i / 8][i % 8] = (__bf16)pr;
+            dsb[i / 8][i % 8] = (__bf16)(pr * (dpacc[i] - del4[i / 4][i % 4]));
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, -lse4[i / 4][i % 4]));
+            pb[i / 8][i % 8] = (__bf16)pr;
+            dsb[i / 8][i % 8] = (__bf16)(pr * (dpacc[i] - del4[i / 4][i % 4]));
           }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // Phase 5: dV^T += dO^T P, dK^T += Q^T dS.  k-slots of step t are rows 16t + 4*g2 + [0,4)
+        // and 16t + 8 + 4*g2 + [0,4), matching pb/dsb
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tdo[t][db], pb[t], dvacc[db], 0, 0, 0);
+            dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[t][db], dsb[t], dkacc[db], 0, 0, 0);
+          }
       }
       if (it + 1 < n_iter) store_stage(buf ^ 1);
       __syncthreads();
@@ -279,8 +308,8 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(const BwdParams p) {
 // ============================================================================================
 template <int D>
 struct DqCfg {
-  static constexpr int BM = kFwdBM;               // 128 query rows per unit (32 per wave)
-  static constexpr int BN = kFwdBN;               // 64 keys per LDS tile
+  static constexpr int BM = kDqBM;                // 128 query rows per unit (32 per wave)
+  static constexpr int BN = kDqBN;                // 64 keys per LDS tile
   static constexpr int KSTRIDE = D * 2 + 32;      // K rows: b128 row reads AND transpose reads
   static constexpr int VSTRIDE = D * 2 + 16;      // V rows: b128 row reads only
   static constexpr int KBYTES = BN * KSTRIDE;
@@ -522,9 +551,9 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   if (cap_kv > INT32_MAX / 64 || cap_q > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: too many tiles");
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
-  int rc = fcp::launch_schedule(true, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
+  int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
-  rc = fcp::launch_schedule(false, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
+  rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
 

@@ -49,6 +49,7 @@ struct FwdParams {
 };
 
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kRescaleThreshold = 8.f;   // log2 units
 
 __device__ inline float lane32_partner_max(float x) {
   // v_permlane32_swap exchanges the upper half of the first operand with the lower half of
@@ -196,19 +197,53 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
       if (wave_sees) {
         const unsigned char* kb = smem + buf * C::STAGE;
         const unsigned char* vb = kb + C::KBYTES;
+        // LDS fragments are requested a whole group ahead of the MFMAs that use them (the
+        // sched_barriers keep the compiler from re-serialising read -> wait -> MFMA), so the LDS
+        // latency is paid once per group instead of once per MFMA.
+        // A operand of O^T += V^T P^T: rows d = 32*db + l32; its 8 k-slots are keys
+        // 16t + {4*g2 + [0,4), 8 + 4*g2 + [0,4)}.  Transpose read: a lane supplies the address of row
+        // (l%16)/4, channels 4*(l%4) + [0,4) of its 16-lane block; block b covers channels
+        // 16*(b%2) + [0,16) for key group g2 = b/2.
+        const unsigned char* vbase = vb + (4 * g2 + ((lane & 15) >> 2)) * C::VSTRIDE +
+                                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+        auto load_vt = [&](int t, bf16x8 (&dst)[D / 32]) {
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db) {
+            const unsigned char* a0 = vbase + (16 * t) * C::VSTRIDE + 64 * db;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(a0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)(a0 + 8 * C::VSTRIDE));
+            dst[db] = __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi),
+                                              0, 1, 2, 3, 4, 5, 6, 7);
+          }
+        };
         // ---- S^T[key, q] = K Q^T ------------------------------------------------------
         f32x16 sacc[2];
+        bf16x8 ka[2][D / 16];
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk) {
+        for (int ks = 0; ks < D / 16; ++ks)
+          ka[0][ks] = *reinterpret_cast<const bf16x8*>(kb + l32 * C::KSTRIDE + 16 * g2 + 32 * ks);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int i = 0; i < 16; ++i) sacc[kbk][i] = 0.f;
-          const unsigned char* krow = kb + (32 * kbk + l32) * C::KSTRIDE + 16 * g2;
+        for (int ks = 0; ks < D / 16; ++ks)
+          ka[1][ks] = *reinterpret_cast<const bf16x8*>(kb + (32 + l32) * C::KSTRIDE + 16 * g2 + 32 * ks);
+        {
+          const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][0], qf[0], z, 0, 0, 0);
 #pragma unroll
-          for (int ks = 0; ks < D / 16; ++ks) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
-            sacc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[ks], sacc[kbk], 0, 0, 0);
-          }
+          for (int ks = 1; ks < D / 16; ++ks)
+            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][ks], qf[ks], sacc[0], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[1][0], qf[0], z, 0, 0, 0);
+#pragma unroll
+          for (int ks = 1; ks < D / 16; ++ks)
+            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[1][ks], qf[ks], sacc[1], 0, 0, 0);
         }
+        bf16x8 vt0[D / 32], vt1[D / 32];
+        load_vt(0, vt0);     // lands while the scores are exponentiated
+        load_vt(1, vt1);
+        __builtin_amdgcn_sched_barrier(0);
         // ---- mask + online softmax ------------------------------------------------------
         // register i of block kbk is key 32*kbk + 8*(i/4) + 4*g2 + (i%4) of the tile
         if (need_mask) {
@@ -225,11 +260,20 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
           for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kbk][i]);
-        mx = lane32_partner_max(mx);
-        const float m_new = fmaxf(m_run, mx * p.scale_log2);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-        m_run = m_new;
+        mx = lane32_partner_max(mx) * p.scale_log2;
+        // Lazy rescale: the running maximum is raised only when some row of the wave outgrows it by
+        // 2^kRescaleThreshold; until then probabilities may exceed 1 (by at most that factor).
+        if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleThreshold) != 0) {
+          const float m_new = fmaxf(m_run, mx);
+          const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
+          m_run = m_new;
+          l_run *= alpha;
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        }
+        const float m_use = m_run == -INFINITY ? 0.f : m_run;
         float psum = 0.f;
         bf16x8 pf[4];   // P^T as B operand: k-step t covers keys 16t..16t+15 of the tile
 #pragma unroll
@@ -240,31 +284,21 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
             psum += e;
             pf[2 * kbk + i / 8][i % 8] = (__bf16)e;
           }
-        l_run = l_run * alpha + psum;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        l_run += psum;
+        __builtin_amdgcn_sched_barrier(0);
         // ---- O^T[d, q] += V^T P^T ---------------------------------------------------------
-        // A operand rows d = 32*db + l32; its 8 k-slots are keys 16t + {4*g2 + [0,4), 8 + 4*g2 + [0,4)}.
-        // Transpose read: lane supplies the address of row (l%16)/4, channels 4*(l%4) + [0,4) of its
-        // 16-lane block; block b covers channels 16*(b%2) + [0,16) for key group g2 = b/2.
-        const unsigned char* vbase = vb + (4 * g2 + ((lane & 15) >> 2)) * C::VSTRIDE +
-                                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+        bf16x8 vt2[D / 32], vt3[D / 32];
+        load_vt(2, vt2);
+        load_vt(3, vt3);
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt0[db], pf[0], oacc[db], 0, 0, 0);
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            const unsigned char* a0 = vbase + (16 * t) * C::VSTRIDE + 64 * db;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(a0));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(a0 + 8 * C::VSTRIDE));
-            const bf16x4 lo_b = __builtin_bit_cast(bf16x4, lo), hi_b = __builtin_bit_cast(bf16x4, hi);
-            const bf16x8 a = __builtin_shufflevector(lo_b, hi_b, 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[t], oacc[db], 0, 0, 0);
-          }
-        }
+        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt1[db], pf[1], oacc[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt2[db], pf[2], oacc[db], 0, 0, 0);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt3[db], pf[3], oacc[db], 0, 0, 0);
       }
 
       if (it + 1 < n_iter) store_tile(buf ^ 1);
@@ -325,7 +359,7 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap = fcp::q_tile_cap(tq, tkv, n_work, n_parts);
   if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
-  int rc = fcp::launch_schedule(false, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
+  int rc = fcp::launch_schedule(false, fcp::kFwdBM, fcp::kFwdBN, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
                                 lse_part, (int64_t)n_parts * hq * tq, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;

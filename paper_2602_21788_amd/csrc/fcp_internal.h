@@ -37,10 +37,13 @@ struct Tile {                    // forward: a block of query rows of one work i
   int32_t idx;                   // fwd: q-tile index; bwd: (seg << 24) | kv-tile index
 };
 
-constexpr int kFwdBM = 128;      // query rows per forward tile
+constexpr int kFwdBM = 128;      // query rows per forward unit
 constexpr int kFwdBN = 64;       // keys per forward inner step
-constexpr int kBwdBN = 128;      // keys per backward tile
-constexpr int kBwdBM = 32;       // query rows per backward inner step
+constexpr int kDqBM = 128;       // query rows per dQ unit
+constexpr int kDqBN = 64;        // keys per dQ inner step
+constexpr int kBwdBN = 128;      // keys per dK/dV unit
+constexpr int kBwdBM = 32;       // query rows per dK/dV inner step
+constexpr int kMinQTile = 128;   // smallest query tile of any kernel (sizes the tile lists)
 
 // Upper bounds on the number of tiles of a valid plan (anything beyond is dropped and
 // counted as rejected).  Query tiles: every (row, slot) belongs to at most one item, and over
@@ -71,9 +74,10 @@ inline const Tile* sched_tiles(const void* region, int64_t n_work) {
                                        sched_item_off_bytes(n_work) + sched_flags_bytes(n_work));
 }
 
-// Builds one tile list in `region` (key tiles if `key_tiles`, else query tiles) and, when
+// Builds one tile list in `region` (tiles of `tile` keys if `key_tiles`, else of `tile` query rows;
+// `inner` is the block size of the other dimension used for the cost) and, when
 // lse_fill is given, fills it with -inf.
-int launch_schedule(bool key_tiles, const fcp_work_desc* work, int64_t n_work,
+int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
                     int64_t lse_fill_n, hipStream_t stream);

@@ -18,7 +18,7 @@ namespace {
 
 constexpr int kSchedThreads = 1024;
 constexpr int kBuckets = 2048;
-constexpr int kMaxExclusiveScan = 4096;   // beyond this many items the O(n^2) overlap scan is skipped
+constexpr int kMaxExclusiveScan = 1024;   // beyond this many items the all-pairs overlap scan is skipped
 
 struct ItemInfo {
   bool ok;
@@ -55,36 +55,37 @@ __device__ inline int32_t visible_len(const fcp_work_desc& w, int s, int32_t las
   return (int32_t)v;
 }
 
-__device__ inline int32_t fwd_cost(const fcp_work_desc& w, int32_t qt) {
-  int32_t last_row = min((qt + 1) * kFwdBM, w.q_len) - 1;
+// query tile qt (of `tile` rows): cost = key blocks (of `inner` keys) its last row sees
+__device__ inline int32_t fwd_cost(const fcp_work_desc& w, int32_t qt, int32_t tile, int32_t inner) {
+  int32_t last_row = min((qt + 1) * tile, w.q_len) - 1;
   int32_t c = 0;
-  for (int s = 0; s < w.n_seg; ++s) c += ceil_div(visible_len(w, s, last_row), kFwdBN);
+  for (int s = 0; s < w.n_seg; ++s) c += ceil_div(visible_len(w, s, last_row), inner);
   return c;
 }
 
-// backward: cost of key tile kt of segment s = query blocks that see its first key
-__device__ inline int32_t bwd_cost(const fcp_work_desc& w, int s, int32_t kt) {
-  const int64_t first_k_pos = (int64_t)w.k_seq_start[s] + (int64_t)kt * kBwdBN;
+// key tile kt (of `tile` keys) of segment s: cost = query blocks (of `inner` rows) that see its first key
+__device__ inline int32_t bwd_cost(const fcp_work_desc& w, int s, int32_t kt, int32_t tile, int32_t inner) {
+  const int64_t first_k_pos = (int64_t)w.k_seq_start[s] + (int64_t)kt * tile;
   int64_t first_row = first_k_pos - w.q_seq_start;
   if (first_row < 0) first_row = 0;
   const int64_t rows = (int64_t)w.q_len - first_row;
-  return rows <= 0 ? 0 : (int32_t)((rows + kBwdBM - 1) / kBwdBM);
+  return rows <= 0 ? 0 : (int32_t)((rows + inner - 1) / inner);
 }
 
 __device__ inline ItemInfo item_info(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
                                      int32_t tq, int32_t tkv, int32_t n_parts, bool backward,
-                                     bool check_step) {
+                                     bool check_step, int32_t tile, int32_t inner) {
   ItemInfo r{false, 0, 0, 0};
   r.ok = item_valid(w, cu, n_seqs, tq, tkv, n_parts, check_step);
   if (!r.ok) return r;
   if (!backward) {
-    r.n_tiles = ceil_div(w.q_len, kFwdBM);
-    r.max_cost = fwd_cost(w, r.n_tiles - 1);
+    r.n_tiles = ceil_div(w.q_len, tile);
+    r.max_cost = fwd_cost(w, r.n_tiles - 1, tile, inner);
   } else {
-    r.nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), kBwdBN);
-    int32_t nt1 = w.n_seg > 1 ? ceil_div(visible_len(w, 1, w.q_len - 1), kBwdBN) : 0;
+    r.nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), tile);
+    int32_t nt1 = w.n_seg > 1 ? ceil_div(visible_len(w, 1, w.q_len - 1), tile) : 0;
     r.n_tiles = r.nt0 + nt1;
-    r.max_cost = ceil_div(w.q_len, kBwdBM);
+    r.max_cost = ceil_div(w.q_len, inner);
   }
   return r;
 }
@@ -112,7 +113,7 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32
 }
 
 __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
-    int backward, int check_step, const fcp_work_desc* __restrict__ work, int32_t n_work,
+    int backward, int check_step, int32_t tile, int32_t inner, const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
     int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
     float* lse_fill, int64_t lse_fill_n) {
@@ -125,6 +126,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
   __shared__ int32_t s_wave[kSchedThreads / 64];
   __shared__ int32_t s_hist[kBuckets];
   __shared__ int32_t s_max, s_rej, s_carry;
+  __shared__ int32_t s_rng[kMaxExclusiveScan][7];   // seq (-1 = invalid), q range, two key ranges
   const int tid = threadIdx.x;
   if (tid == 0) { s_max = 0; s_rej = 0; s_carry = 0; }
   for (int b = tid; b < kBuckets; b += kSchedThreads) s_hist[b] = 0;
@@ -136,7 +138,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     int32_t cnt = 0;
     if (i < n_work) {
       const fcp_work_desc w = work[i];
-      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0);
+      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0, tile, inner);
       if (!info.ok) atomicAdd(&s_rej, 1);
       cnt = info.n_tiles;
       if (info.max_cost > 0) atomicMax(&s_max, info.max_cost);
@@ -150,31 +152,44 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     __syncthreads();
   }
   // Exclusivity flags: an item whose query rows (key segments) no other valid item of this
-  // launch touches lets the backward kernels add to dQ (dK/dV) without atomics.
-  for (int32_t i = tid; i < n_work; i += kSchedThreads) {
-    int32_t flags = 0;
-    if (n_work <= kMaxExclusiveScan) {
+  // launch touches lets the backward kernels add to dQ (dK/dV) without atomics.  The items'
+  // ranges are staged in LDS so that the all-pairs scan does not wait on global memory.
+  if (n_work <= kMaxExclusiveScan) {
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) {
       const fcp_work_desc a = work[i];
-      if (item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0)) {
+      const bool ok = item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0);
+      s_rng[i][0] = ok ? a.seq : -1;
+      s_rng[i][1] = a.q_local_off;
+      s_rng[i][2] = a.q_local_off + a.q_len;
+      s_rng[i][3] = a.k_seq_start[0];
+      s_rng[i][4] = a.k_seq_start[0] + a.k_len[0];
+      s_rng[i][5] = a.n_seg > 1 ? a.k_seq_start[1] : 0;
+      s_rng[i][6] = a.n_seg > 1 ? a.k_seq_start[1] + a.k_len[1] : 0;   // empty range when absent
+    }
+    __syncthreads();
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) {
+      int32_t flags = 0;
+      if (s_rng[i][0] >= 0) {
         flags = kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive;
-        if (a.n_seg == 2 && a.k_seq_start[0] + a.k_len[0] > a.k_seq_start[1]) flags &= kFlagQExclusive;
+        const int32_t seq = s_rng[i][0], q0 = s_rng[i][1], q1 = s_rng[i][2];
+        const int32_t k0[2] = {s_rng[i][3], s_rng[i][5]}, k1[2] = {s_rng[i][4], s_rng[i][6]};
+        if (k0[0] < k1[1] && k0[1] < k1[0]) flags &= kFlagQExclusive;   // own segments overlap
         for (int32_t j = 0; j < n_work; ++j) {
-          if (j == i) continue;
-          const fcp_work_desc b = work[j];
-          if (!item_valid(b, cu, n_seqs, tq, tkv, n_parts, check_step != 0)) continue;
-          if (a.q_local_off < b.q_local_off + b.q_len && b.q_local_off < a.q_local_off + a.q_len)
-            flags &= ~kFlagQExclusive;
-          if (a.seq == b.seq) {
-            for (int sa = 0; sa < a.n_seg; ++sa)
-              for (int sb = 0; sb < b.n_seg; ++sb)
-                if (a.k_seq_start[sa] < b.k_seq_start[sb] + b.k_len[sb] &&
-                    b.k_seq_start[sb] < a.k_seq_start[sa] + a.k_len[sa])
-                  flags &= ~(sa == 0 ? kFlagSeg0Exclusive : kFlagSeg1Exclusive);
+          if (j == i || s_rng[j][0] < 0) continue;
+          if (q0 < s_rng[j][2] && s_rng[j][1] < q1) flags &= ~kFlagQExclusive;
+          if (s_rng[j][0] == seq) {
+#pragma unroll
+            for (int sa = 0; sa < 2; ++sa) {
+              if ((k0[sa] < s_rng[j][4] && s_rng[j][3] < k1[sa]) || (k0[sa] < s_rng[j][6] && s_rng[j][5] < k1[sa]))
+                flags &= ~(sa == 0 ? kFlagSeg0Exclusive : kFlagSeg1Exclusive);
+            }
           }
         }
       }
+      item_flags[i] = flags;
     }
-    item_flags[i] = flags;
+  } else {
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = 0;
   }
   const int32_t total_tiles = s_carry;
   const int32_t n_tiles = min(total_tiles, tile_cap);
@@ -198,13 +213,13 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     out.work = lo;
     if (!backward) {
       out.idx = local;
-      return fwd_cost(w, local);
+      return fwd_cost(w, local, tile, inner);
     }
-    const int32_t nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), kBwdBN);
+    const int32_t nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), tile);
     const int s = local >= nt0 ? 1 : 0;
     const int32_t kt = local - (s ? nt0 : 0);
     out.idx = (s << 24) | kt;
-    return bwd_cost(w, s, kt);
+    return bwd_cost(w, s, kt, tile, inner);
   };
 
   for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
@@ -243,8 +258,8 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
 }  // namespace
 
 int64_t q_tile_cap(int32_t tq, int32_t tkv, int64_t n_work, int32_t n_parts) {
-  const int64_t by_slots = (int64_t)n_parts * ((tq + kFwdBM - 1) / kFwdBM);
-  const int64_t by_tokens = (int64_t)((tkv + kFwdBM - 1) / kFwdBM);
+  const int64_t by_slots = (int64_t)n_parts * ((tq + kMinQTile - 1) / kMinQTile);
+  const int64_t by_tokens = (int64_t)((tkv + kMinQTile - 1) / kMinQTile);
   return n_work + (by_slots < by_tokens ? by_slots : by_tokens);
 }
 
@@ -252,7 +267,7 @@ int64_t kv_tile_cap(int32_t tkv, int64_t n_work) {
   return 2 * n_work + 2 * (int64_t)((tkv + kBwdBN - 1) / kBwdBN);
 }
 
-int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
+int launch_schedule(bool backward, int32_t tile, int32_t inner, const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
                     int64_t lse_fill_n, hipStream_t stream) {
@@ -268,7 +283,7 @@ int launch_schedule(bool backward, const fcp_work_desc* work, int64_t n_work,
     if (fill_blocks < 1) fill_blocks = 1;
   }
   hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks), dim3(kSchedThreads), 0, stream,
-                     backward ? 1 : 0, lse_fill ? 1 : 0, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
+                     backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
                      (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
