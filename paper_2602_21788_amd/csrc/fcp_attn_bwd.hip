@@ -112,16 +112,12 @@ __global__ __launch_bounds__(256, 1) void dkv_kernel(const BwdParams p) {
     if (unit >= n_units) break;
     const int tile_i = unit / kvh_here;
     const int kvh = xcd * kvh_here + unit % kvh_here;
-    const Tile tile = p.tiles[tile_i];
-    const fcp_work_desc w = p.work[tile.work];
-    const int seg = tile.idx >> 24, kt = tile.idx & 0xffffff;
-    const bool exclusive = (p.flags[tile.work] & (seg ? kFlagSeg1Exclusive : kFlagSeg0Exclusive)) != 0;
-
-    const int vis_len = max(0, min(w.k_len[seg], w.q_seq_start + w.q_len - w.k_seq_start[seg]));
-    const int key0 = kt * C::BN;
-    const int n_keys = min(C::BN, vis_len - key0);             // >= 1 by construction
-    const int k_pos0 = w.k_seq_start[seg] + key0;
-    const int64_t kv_row0 = (int64_t)p.cu[w.seq] + w.k_seq_start[seg] + key0;
+    const KTile t = *reinterpret_cast<const KTile*>(&p.tiles[tile_i]);
+    struct { int32_t q_local_off, q_seq_start, q_len; } w = {t.q_local_off, t.q_seq_start, t.q_len};
+    const bool exclusive = (t.flags & kFlagSeg0Exclusive) != 0;
+    const int n_keys = t.n_keys;                               // >= 1 by construction
+    const int k_pos0 = t.k_pos0;
+    const int64_t kv_row0 = t.kv_row0;
     const int my_key = 32 * wave + l32;
     const int my_key_ld = min(my_key, n_keys - 1);
     const int my_k_pos = k_pos0 + my_key;
@@ -345,25 +341,23 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(const BwdParams p) {
     const int tile_i = unit / heads_here;
     const int head = xcd * heads_here + unit % heads_here;
     const int kvh = head / G;
-    const Tile tile = p.tiles[tile_i];
-    const fcp_work_desc w = p.work[tile.work];
-    const bool exclusive = (p.flags[tile.work] & kFlagQExclusive) != 0;
+    const QTile t = *reinterpret_cast<const QTile*>(&p.tiles[tile_i]);
+    const bool exclusive = (t.flags & kFlagQExclusive) != 0;
 
-    const int q_r0 = tile.idx * C::BM;
-    const int rows_here = min(C::BM, w.q_len - q_r0);
-    const int wave_r0 = q_r0 + wave * 32;
-    const bool wave_active = wave * 32 < rows_here;
+    const int rows_here = t.rows;
+    const int wave_r0 = wave * 32;
+    const bool wave_active = wave_r0 < rows_here;
     const int my_row = wave_r0 + l32;
-    const bool row_valid = my_row < w.q_len;
-    const int row_ld = min(my_row, w.q_len - 1);
-    const int q_pos = w.q_seq_start + my_row;
-    const int wave_first_pos = w.q_seq_start + wave_r0;
-    const int wave_last_pos = w.q_seq_start + min(wave_r0 + 31, w.q_len - 1);
+    const bool row_valid = my_row < rows_here;
+    const int row_ld = min(my_row, rows_here - 1);
+    const int q_pos = t.q_pos0 + my_row;
+    const int wave_first_pos = t.q_pos0 + wave_r0;
+    const int wave_last_pos = t.q_pos0 + min(wave_r0 + 31, rows_here - 1);
 
     // Q and dO fragments: B operands (lane = query column), channels 16*ks + 8*g2 + [0,8)
     bf16x8 qf[D / 16], dof[D / 16];
     {
-      const int64_t off = ((int64_t)(w.q_local_off + row_ld) * p.hq + head) * D + 8 * g2;
+      const int64_t off = ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
         qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
@@ -372,22 +366,20 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(const BwdParams p) {
     }
     float lse2, delta;
     {
-      const int64_t off = (int64_t)head * p.tq + w.q_local_off + row_ld;
+      const int64_t off = (int64_t)head * p.tq + t.q_row0 + row_ld;
       const float l = p.lse[off];
       lse2 = l == -INFINITY ? INFINITY : l * kLog2e;
       delta = p.delta[off];
     }
 
-    const int last_pos = w.q_seq_start + q_r0 + rows_here - 1;
-    int vis[2], nt[2];
+    int vis[2], nt[2], k_seg_pos[2];
     int64_t kv_row0[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      int vl = 0;
-      if (s < w.n_seg) vl = max(0, min(w.k_len[s], last_pos - w.k_seq_start[s] + 1));
-      vis[s] = vl;
-      nt[s] = (vl + C::BN - 1) / C::BN;
-      kv_row0[s] = (int64_t)p.cu[w.seq] + w.k_seq_start[s];
+      vis[s] = t.vis[s];
+      nt[s] = (vis[s] + C::BN - 1) / C::BN;
+      kv_row0[s] = t.kv_row0[s];
+      k_seg_pos[s] = t.k_pos0[s];
     }
     const int n_iter = nt[0] + nt[1];
 
@@ -433,7 +425,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(const BwdParams p) {
       if (it + 1 < n_iter) issue_loads(it + 1);
       const int s = it >= nt[0] ? 1 : 0;
       const int kt = it - (s ? nt[0] : 0);
-      const int k_pos0 = w.k_seq_start[s] + kt * C::BN;
+      const int k_pos0 = k_seg_pos[s] + kt * C::BN;
       const int n_valid = min(C::BN, vis[s] - kt * C::BN);
       const bool wave_sees = wave_active && k_pos0 <= wave_last_pos;
       const bool need_mask = (k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN);
@@ -487,7 +479,7 @@ __global__ __launch_bounds__(256, 2) void dq_kernel(const BwdParams p) {
 
     // epilogue: dQ^T [channel x query] * scale -> accumulator rows
     if (row_valid) {
-      float* dqp = p.dq + ((int64_t)(w.q_local_off + my_row) * p.hq + head) * D + 4 * g2;
+      float* dqp = p.dq + ((int64_t)(t.q_row0 + my_row) * p.hq + head) * D + 4 * g2;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -551,9 +543,9 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   if (cap_kv > INT32_MAX / 64 || cap_q > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: too many tiles");
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
-  int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
+  int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
-  rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
+  rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
 

@@ -32,14 +32,12 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 struct FwdParams {
   const uint16_t* q;
   const uint16_t* k;
   const uint16_t* v;
-  const int32_t* cu;
-  const fcp_work_desc* work;
-  const SchedHeader* hdr_ro;
   SchedHeader* hdr;
   const Tile* tiles;
   float* o_part;
@@ -75,13 +73,21 @@ struct FwdCfg {
   static constexpr int CHUNKS = BN * D * 2 / 16;  // 16-byte pieces per tensor tile
   static constexpr int CPT = CHUNKS / 256;        // pieces per thread
   static constexpr int CPR = D * 2 / 16;          // pieces per row
+  static constexpr int RPP = 256 / CPR;           // rows covered by one pass of the 256 threads
 };
 
+// On this chip plain VALU instructions do not overlap with MFMAs (measured: an MFMA plus n
+// fp32 FMAs takes the sum of both), only the transcendental unit does.  The loop therefore
+// spends as few VALU instructions per MFMA as it can: global loads go through buffer
+// instructions whose per-tile offset is a scalar (out-of-range rows read as zero, so there is
+// no clamping), LDS addresses are per-thread constants plus immediates, and the accumulator
+// rescale is lazy.
 template <int D>
 __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
   using C = FwdCfg<D>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int32_t s_unit;
+  __shared__ int32_t s_next_unit;
+  __shared__ int32_t s_rec[16];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -92,53 +98,76 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
   const bool per_xcd = (p.hq % kNumXcd) == 0;
   const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
   const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
-  const int n_tiles = p.hdr_ro->n_tiles;
-  const int n_units = n_tiles * heads_here;
+  const int n_units = p.hdr->n_tiles * heads_here;
+  const int32_t* rec_words = reinterpret_cast<const int32_t*>(p.tiles);
+
+  // Unit fetch, two deep: wave 0 holds the atomic for the unit after next in flight and the
+  // record of the next unit in flight while the block computes the current one.
+  int32_t pend = 0, recw = 0;
+  if (wave == 0) {
+    int32_t v0 = 0;
+    if (lane == 0) v0 = atomicAdd(&p.hdr->counter[xcd], 1);
+    const int32_t u0 = __builtin_amdgcn_readfirstlane(v0);
+    if (lane == 0) pend = atomicAdd(&p.hdr->counter[xcd], 1);
+    if (lane < 16) s_rec[lane] = u0 < n_units ? rec_words[(u0 / heads_here) * 16 + lane] : 0;
+    if (lane == 0) s_next_unit = u0;
+  }
+  __syncthreads();
+
+  // per-thread constants of the K/V tile movement
+  const int ld_r = tid / C::CPR, ld_c = tid % C::CPR;
+  const int lds_k_thread = ld_r * C::KSTRIDE + ld_c * 16;
+  const int lds_v_thread = C::KBYTES + ld_r * C::VSTRIDE + ld_c * 16;
+  const int kv_row_bytes = p.hkv * D * 2;
+  const int voff0 = ld_r * kv_row_bytes + ld_c * 16;
 
   for (;;) {
-    if (tid == 0) s_unit = atomicAdd(&p.hdr->counter[xcd], 1);
-    __syncthreads();
-    const int unit = __builtin_amdgcn_readfirstlane(s_unit);
-    __syncthreads();
+    const int unit = __builtin_amdgcn_readfirstlane(s_next_unit);
     if (unit >= n_units) break;
-    const int tile_i = unit / heads_here;
+    QTile t;
+    {
+      int32_t* tw = reinterpret_cast<int32_t*>(&t);
+#pragma unroll
+      for (int i = 0; i < 11; ++i) tw[i] = __builtin_amdgcn_readfirstlane(s_rec[i]);
+    }
     const int head = xcd * heads_here + unit % heads_here;
     const int kvh = head / G;
-    const Tile tile = p.tiles[tile_i];
-    const fcp_work_desc w = p.work[tile.work];
+    int32_t idx1 = 0;
+    if (wave == 0) {   // next unit's record and the following unit's number start their trips now
+      idx1 = __builtin_amdgcn_readfirstlane(pend);
+      if (lane == 0) pend = atomicAdd(&p.hdr->counter[xcd], 1);
+      recw = (lane < 16 && idx1 < n_units) ? rec_words[(idx1 / heads_here) * 16 + lane] : 0;
+    }
 
-    const int q_r0 = tile.idx * C::BM;                       // first row of the unit in the item
-    const int rows_here = min(C::BM, w.q_len - q_r0);
-    const int wave_r0 = q_r0 + wave * 32;
-    const bool wave_active = wave * 32 < rows_here;
+    const int wave_r0 = wave * 32;
+    const bool wave_active = wave_r0 < t.rows;
     const int my_row = wave_r0 + l32;
-    const bool row_valid = my_row < w.q_len;
-    const int row_ld = min(my_row, w.q_len - 1);
-    const int q_pos = w.q_seq_start + my_row;
-    const int wave_first_pos = w.q_seq_start + wave_r0;
-    const int wave_last_pos = w.q_seq_start + min(wave_r0 + 31, w.q_len - 1);
+    const bool row_valid = my_row < t.rows;
+    const int row_ld = min(my_row, t.rows - 1);
+    const int q_pos = t.q_pos0 + my_row;
+    const int wave_first_pos = t.q_pos0 + wave_r0;
+    const int wave_last_pos = t.q_pos0 + min(wave_r0 + 31, t.rows - 1);
 
     // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16*ks + 8*g2 + [0,8)
     bf16x8 qf[D / 16];
     {
-      const uint16_t* qp = p.q + ((int64_t)(w.q_local_off + row_ld) * p.hq + head) * D + 8 * g2;
+      const uint16_t* qp = p.q + ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
 
-    // visible key range per segment for this unit
-    const int last_pos = w.q_seq_start + q_r0 + rows_here - 1;
-    int vis[2], nt[2];
-    int64_t kv_row0[2];
+    // Key segments: a buffer resource per segment whose extent ends with the last visible key,
+    // so rows past it load as zeros.
+    const int nt0 = (t.vis[0] + C::BN - 1) / C::BN, nt1 = (t.vis[1] + C::BN - 1) / C::BN;
+    const int n_iter = nt0 + nt1;
+    __amdgpu_buffer_rsrc_t rk[2], rv[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
-      int vl = 0;
-      if (s < w.n_seg) vl = max(0, min(w.k_len[s], last_pos - w.k_seq_start[s] + 1));
-      vis[s] = vl;
-      nt[s] = (vl + C::BN - 1) / C::BN;
-      kv_row0[s] = (int64_t)p.cu[w.seq] + w.k_seq_start[s];
+      const int64_t off = ((int64_t)t.kv_row0[s] * p.hkv + kvh) * D;
+      const int bytes = t.vis[s] > 0 ? (t.vis[s] - 1) * kv_row_bytes + D * 2 : 0;
+      rk[s] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.k + off), (short)0, bytes, 0x00020000);
+      rv[s] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.v + off), (short)0, bytes, 0x00020000);
     }
-    const int n_iter = nt[0] + nt[1];
 
     f32x16 oacc[D / 32];
 #pragma unroll
@@ -151,28 +180,27 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
     // ---- K/V tile movement ---------------------------------------------------------
     u32x4 kreg[C::CPT], vreg[C::CPT];
     auto issue_loads = [&](int it) {
-      const int s = it >= nt[0] ? 1 : 0;
-      const int kt = it - (s ? nt[0] : 0);
-      const int vl = vis[s];
+      const int s = it >= nt0 ? 1 : 0;
+      const int soff = (it - (s ? nt0 : 0)) * (C::BN * kv_row_bytes);
 #pragma unroll
       for (int c = 0; c < C::CPT; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        const int key = min(kt * C::BN + r, vl - 1);          // clamp: masked anyway
-        const int64_t off = ((kv_row0[s] + key) * p.hkv + kvh) * D + col * 8;
-        kreg[c] = *reinterpret_cast<const u32x4*>(p.k + off);
-        vreg[c] = *reinterpret_cast<const u32x4*>(p.v + off);
+        const int voff = voff0 + c * C::RPP * kv_row_bytes;
+        if (s == 0) {
+          kreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rk[0], voff, soff, 0);
+          vreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rv[0], voff, soff, 0);
+        } else {
+          kreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rk[1], voff, soff, 0);
+          vreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rv[1], voff, soff, 0);
+        }
       }
     };
     auto store_tile = [&](int buf) {
-      unsigned char* kb = smem + buf * C::STAGE;
-      unsigned char* vb = kb + C::KBYTES;
+      unsigned char* kb = smem + buf * C::STAGE + lds_k_thread;
+      unsigned char* vb = smem + buf * C::STAGE + lds_v_thread;
 #pragma unroll
       for (int c = 0; c < C::CPT; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        *reinterpret_cast<u32x4*>(kb + r * C::KSTRIDE + col * 16) = kreg[c];
-        *reinterpret_cast<u32x4*>(vb + r * C::VSTRIDE + col * 16) = vreg[c];
+        *reinterpret_cast<u32x4*>(kb + c * C::RPP * C::KSTRIDE) = kreg[c];
+        *reinterpret_cast<u32x4*>(vb + c * C::RPP * C::VSTRIDE) = vreg[c];
       }
     };
 
@@ -186,10 +214,10 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
       const int buf = it & 1;
       if (it + 1 < n_iter) issue_loads(it + 1);
 
-      const int s = it >= nt[0] ? 1 : 0;
-      const int kt = it - (s ? nt[0] : 0);
-      const int k_pos0 = w.k_seq_start[s] + kt * C::BN;       // position of the tile's first key
-      const int n_valid = min(C::BN, vis[s] - kt * C::BN);     // keys of the tile inside the segment
+      const int s = it >= nt0 ? 1 : 0;
+      const int kt = it - (s ? nt0 : 0);
+      const int k_pos0 = t.k_pos0[s] + kt * C::BN;            // position of the tile's first key
+      const int n_valid = min(C::BN, t.vis[s] - kt * C::BN);   // keys of the tile inside the segment
       // wave-uniform: does this wave see anything in the tile / need the element mask?
       const bool wave_sees = wave_active && k_pos0 <= wave_last_pos;
       const bool need_mask = (k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN);
@@ -198,18 +226,17 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         const unsigned char* kb = smem + buf * C::STAGE;
         const unsigned char* vb = kb + C::KBYTES;
         // LDS fragments are requested a whole group ahead of the MFMAs that use them (the
-        // sched_barriers keep the compiler from re-serialising read -> wait -> MFMA), so the LDS
-        // latency is paid once per group instead of once per MFMA.
+        // sched_barriers keep the compiler from re-serialising read -> wait -> MFMA).
         // A operand of O^T += V^T P^T: rows d = 32*db + l32; its 8 k-slots are keys
         // 16t + {4*g2 + [0,4), 8 + 4*g2 + [0,4)}.  Transpose read: a lane supplies the address of row
         // (l%16)/4, channels 4*(l%4) + [0,4) of its 16-lane block; block b covers channels
         // 16*(b%2) + [0,16) for key group g2 = b/2.
         const unsigned char* vbase = vb + (4 * g2 + ((lane & 15) >> 2)) * C::VSTRIDE +
                                      (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-        auto load_vt = [&](int t, bf16x8 (&dst)[D / 32]) {
+        auto load_vt = [&](int tt, bf16x8 (&dst)[D / 32]) {
 #pragma unroll
           for (int db = 0; db < D / 32; ++db) {
-            const unsigned char* a0 = vbase + (16 * t) * C::VSTRIDE + 64 * db;
+            const unsigned char* a0 = vbase + (16 * tt) * C::VSTRIDE + 64 * db;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (__attribute__((address_space(3))) s16x4*)(a0));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -221,13 +248,13 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         // ---- S^T[key, q] = K Q^T ------------------------------------------------------
         f32x16 sacc[2];
         bf16x8 ka[2][D / 16];
+        const unsigned char* krow = kb + l32 * C::KSTRIDE + 16 * g2;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks)
-          ka[0][ks] = *reinterpret_cast<const bf16x8*>(kb + l32 * C::KSTRIDE + 16 * g2 + 32 * ks);
+        for (int ks = 0; ks < D / 16; ++ks) ka[0][ks] = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < D / 16; ++ks)
-          ka[1][ks] = *reinterpret_cast<const bf16x8*>(kb + (32 + l32) * C::KSTRIDE + 16 * g2 + 32 * ks);
+          ka[1][ks] = *reinterpret_cast<const bf16x8*>(krow + 32 * C::KSTRIDE + 32 * ks);
         {
           const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][0], qf[0], z, 0, 0, 0);
@@ -276,6 +303,9 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         const float m_use = m_run == -INFINITY ? 0.f : m_run;
         float psum = 0.f;
         bf16x8 pf[4];   // P^T as B operand: k-step t covers keys 16t..16t+15 of the tile
+        // the row sum is taken over the unrounded fp32 values: summing the bf16-rounded ones
+        // (v_dot2c) would halve the adds but costs up to 2^-9 relative on a peaked row, i.e.
+        // more than the 1e-3 the LSE has to hold
 #pragma unroll
         for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
@@ -309,8 +339,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
     const float l_tot = lane32_partner_sum(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (row_valid) {
-      float* orow = p.o_part + (int64_t)w.step * ((int64_t)p.tq * p.hq * D) +
-                    ((int64_t)(w.q_local_off + my_row) * p.hq + head) * D;
+      float* orow = p.o_part + (int64_t)t.step * ((int64_t)p.tq * p.hq * D) +
+                    ((int64_t)(t.q_row0 + my_row) * p.hq + head) * D;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -321,9 +351,15 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         }
       if (g2 == 0) {
         const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-        p.lse_part[(int64_t)w.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + w.q_local_off + my_row] = lse;
+        p.lse_part[(int64_t)t.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
       }
     }
+    // hand the next unit to the block
+    if (wave == 0) {
+      if (lane < 16) s_rec[lane] = recw;
+      if (lane == 0) s_next_unit = idx1;
+    }
+    __syncthreads();
   }
 }
 
@@ -359,15 +395,14 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap = fcp::q_tile_cap(tq, tkv, n_work, n_parts);
   if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
-  int rc = fcp::launch_schedule(false, fcp::kFwdBM, fcp::kFwdBN, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
+  int rc = fcp::launch_schedule(false, fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
                                 lse_part, (int64_t)n_parts * hq * tq, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
 
   fcp::FwdParams p;
   p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v;
-  p.cu = cu_seqlens_kv; p.work = work;
-  p.hdr_ro = fcp::sched_header(scratch); p.hdr = (fcp::SchedHeader*)scratch;
+  p.hdr = (fcp::SchedHeader*)scratch;
   p.tiles = fcp::sched_tiles(scratch, n_work);
   p.o_part = o_part; p.lse_part = lse_part;
   p.tq = tq; p.hq = hq; p.hkv = hkv;

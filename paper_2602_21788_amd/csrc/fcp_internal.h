@@ -32,10 +32,29 @@ struct SchedHeader {
 };                               // 64 bytes
 static_assert(sizeof(SchedHeader) == 64, "header size");
 
-struct Tile {                    // forward: a block of query rows of one work item
-  int32_t work;                  // backward: a block of keys of one segment of one work item
-  int32_t idx;                   // fwd: q-tile index; bwd: (seg << 24) | kv-tile index
+// One schedulable tile, fully resolved by the scheduler so that an attention kernel needs a
+// single 64-byte read per unit (no dependent loads of work item and cu_seqlens).
+struct QTile {                   // a block of query rows of one work item (forward, dQ)
+  int32_t q_row0;                // local row of the first query row (q_local_off + offset)
+  int32_t q_pos0;                // its position in the sequence
+  int32_t rows;                  // rows in the block
+  int32_t step;                  // partial slot
+  int32_t kv_row0[2];            // pool row of the first key of each segment
+  int32_t k_pos0[2];             // its position in the sequence
+  int32_t vis[2];                // keys of the segment that the block's last row sees (0 = none)
+  int32_t flags;                 // kFlag* of the work item
+  int32_t pad[5];
 };
+struct KTile {                   // a block of keys of one segment of one work item (dK/dV)
+  int32_t kv_row0;               // pool row of the first key
+  int32_t k_pos0;                // its position in the sequence
+  int32_t n_keys;                // keys in the block that some row of the item sees
+  int32_t q_local_off, q_seq_start, q_len;   // the item's query rows
+  int32_t flags;                 // kFlagSeg0Exclusive set iff no other item touches these keys
+  int32_t pad[9];
+};
+static_assert(sizeof(QTile) == 64 && sizeof(KTile) == 64, "tile records are 16 words");
+struct Tile { int32_t w[16]; };  // storage type of the list
 
 constexpr int kFwdBM = 128;      // query rows per forward unit
 constexpr int kFwdBN = 64;       // keys per forward inner step
@@ -75,9 +94,11 @@ inline const Tile* sched_tiles(const void* region, int64_t n_work) {
 }
 
 // Builds one tile list in `region` (tiles of `tile` keys if `key_tiles`, else of `tile` query rows;
-// `inner` is the block size of the other dimension used for the cost) and, when
+// `inner` is the block size of the other dimension used for the cost; kv_row_bytes = hkv*D*2 bounds
+// the segment length so that byte offsets inside a segment fit 31 bits) and, when
 // lse_fill is given, fills it with -inf.
-int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, const fcp_work_desc* work, int64_t n_work,
+int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, int64_t kv_row_bytes,
+                    const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
                     int64_t lse_fill_n, hipStream_t stream);

@@ -30,7 +30,7 @@ struct ItemInfo {
 __device__ inline int32_t ceil_div(int32_t a, int32_t b) { return (a + b - 1) / b; }
 
 __device__ inline bool item_valid(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
-                                  int32_t tq, int32_t tkv, int32_t n_parts, bool check_step) {
+                                  int32_t tq, int32_t tkv, int32_t n_parts, bool check_step, int32_t max_seg_keys) {
   if (w.seq < 0 || w.seq >= n_seqs) return false;
   if (check_step && (w.step < 0 || w.step >= n_parts)) return false;
   if (w.q_len < 1 || w.q_local_off < 0 || w.q_seq_start < 0) return false;
@@ -40,7 +40,7 @@ __device__ inline bool item_valid(const fcp_work_desc& w, const int32_t* cu, int
   const int64_t s0 = cu[w.seq], s1 = cu[w.seq + 1];
   if (s0 < 0 || s1 < s0 || s1 > (int64_t)tkv) return false;
   for (int s = 0; s < w.n_seg; ++s) {
-    if (w.k_seq_start[s] < 0 || w.k_len[s] < 1) return false;
+    if (w.k_seq_start[s] < 0 || w.k_len[s] < 1 || w.k_len[s] > max_seg_keys) return false;
     if (s0 + (int64_t)w.k_seq_start[s] + w.k_len[s] > s1) return false;
   }
   return true;
@@ -74,9 +74,9 @@ __device__ inline int32_t bwd_cost(const fcp_work_desc& w, int s, int32_t kt, in
 
 __device__ inline ItemInfo item_info(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
                                      int32_t tq, int32_t tkv, int32_t n_parts, bool backward,
-                                     bool check_step, int32_t tile, int32_t inner) {
+                                     bool check_step, int32_t tile, int32_t inner, int32_t max_seg_keys) {
   ItemInfo r{false, 0, 0, 0};
-  r.ok = item_valid(w, cu, n_seqs, tq, tkv, n_parts, check_step);
+  r.ok = item_valid(w, cu, n_seqs, tq, tkv, n_parts, check_step, max_seg_keys);
   if (!r.ok) return r;
   if (!backward) {
     r.n_tiles = ceil_div(w.q_len, tile);
@@ -113,7 +113,8 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32
 }
 
 __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
-    int backward, int check_step, int32_t tile, int32_t inner, const fcp_work_desc* __restrict__ work, int32_t n_work,
+    int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys,
+    const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
     int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
     float* lse_fill, int64_t lse_fill_n) {
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     int32_t cnt = 0;
     if (i < n_work) {
       const fcp_work_desc w = work[i];
-      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0, tile, inner);
+      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0, tile, inner, max_seg_keys);
       if (!info.ok) atomicAdd(&s_rej, 1);
       cnt = info.n_tiles;
       if (info.max_cost > 0) atomicMax(&s_max, info.max_cost);
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
   if (n_work <= kMaxExclusiveScan) {
     for (int32_t i = tid; i < n_work; i += kSchedThreads) {
       const fcp_work_desc a = work[i];
-      const bool ok = item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0);
+      const bool ok = item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys);
       s_rng[i][0] = ok ? a.seq : -1;
       s_rng[i][1] = a.q_local_off;
       s_rng[i][2] = a.q_local_off + a.q_len;
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
   while ((s_max >> shift) >= kBuckets) ++shift;
   __syncthreads();
 
-  // Pass 2 and 3 share the decode of a flat tile number into (item, index, cost).
+  // Pass 2 and 3 share the decode of a flat tile number into its resolved record and cost.
   auto decode = [&](int32_t t, Tile& out) -> int32_t {
     int32_t lo = 0, hi = n_work - 1;               // last item with item_off <= t
     while (lo < hi) {
@@ -210,16 +211,36 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     }
     const fcp_work_desc w = work[lo];
     const int32_t local = t - item_off[lo];
-    out.work = lo;
+    const int32_t row0_kv = cu[w.seq];
+    const int32_t fl = item_flags[lo];
+    for (int i = 0; i < 16; ++i) out.w[i] = 0;
     if (!backward) {
-      out.idx = local;
+      QTile* q = reinterpret_cast<QTile*>(&out);
+      const int32_t r0 = local * tile;
+      q->q_row0 = w.q_local_off + r0;
+      q->q_pos0 = w.q_seq_start + r0;
+      q->rows = min(tile, w.q_len - r0);
+      q->step = w.step;
+      for (int sg = 0; sg < 2; ++sg) {
+        q->kv_row0[sg] = sg < w.n_seg ? row0_kv + w.k_seq_start[sg] : 0;
+        q->k_pos0[sg] = sg < w.n_seg ? w.k_seq_start[sg] : 0;
+        q->vis[sg] = sg < w.n_seg ? visible_len(w, sg, r0 + q->rows - 1) : 0;
+      }
+      q->flags = fl;
       return fwd_cost(w, local, tile, inner);
     }
     const int32_t nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), tile);
-    const int s = local >= nt0 ? 1 : 0;
-    const int32_t kt = local - (s ? nt0 : 0);
-    out.idx = (s << 24) | kt;
-    return bwd_cost(w, s, kt, tile, inner);
+    const int sg = local >= nt0 ? 1 : 0;
+    const int32_t kt = local - (sg ? nt0 : 0);
+    KTile* k = reinterpret_cast<KTile*>(&out);
+    k->kv_row0 = row0_kv + w.k_seq_start[sg] + kt * tile;
+    k->k_pos0 = w.k_seq_start[sg] + kt * tile;
+    k->n_keys = min(tile, visible_len(w, sg, w.q_len - 1) - kt * tile);
+    k->q_local_off = w.q_local_off;
+    k->q_seq_start = w.q_seq_start;
+    k->q_len = w.q_len;
+    k->flags = (fl & (sg ? kFlagSeg1Exclusive : kFlagSeg0Exclusive)) ? kFlagSeg0Exclusive : 0;
+    return bwd_cost(w, sg, kt, tile, inner);
   };
 
   for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
@@ -267,7 +288,8 @@ int64_t kv_tile_cap(int32_t tkv, int64_t n_work) {
   return 2 * n_work + 2 * (int64_t)((tkv + kBwdBN - 1) / kBwdBN);
 }
 
-int launch_schedule(bool backward, int32_t tile, int32_t inner, const fcp_work_desc* work, int64_t n_work,
+int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_bytes,
+                    const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
                     int64_t lse_fill_n, hipStream_t stream) {
@@ -283,7 +305,8 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, const fcp_work_d
     if (fill_blocks < 1) fill_blocks = 1;
   }
   hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks), dim3(kSchedThreads), 0, stream,
-                     backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
+                     backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner,
+                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
                      (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
