@@ -20,19 +20,10 @@
 //     transpose read), so V is never transposed in memory;
 //   * key tiles that lie completely below the diagonal skip the mask; key tiles completely
 //     above it are never visited (the loop bound comes from the last row's position).
-#include "fcp_internal.h"
+#include "fcp_device.h"
 
 namespace fcp {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 struct FwdParams {
   const uint16_t* q;
@@ -46,19 +37,7 @@ struct FwdParams {
   float scale_log2;  // softmax_scale * log2(e)
 };
 
-constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kRescaleThreshold = 8.f;   // log2 units
-
-__device__ inline float lane32_partner_max(float x) {
-  // v_permlane32_swap exchanges the upper half of the first operand with the lower half of
-  // the second; with both operands = x every lane ends up holding x of lanes l and l^32.
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
-  return fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
-}
-__device__ inline float lane32_partner_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
-  return __int_as_float(r[0]) + __int_as_float(r[1]);
-}
 
 template <int D>
 struct FwdCfg {
@@ -98,21 +77,8 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
   const bool per_xcd = (p.hq % kNumXcd) == 0;
   const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
   const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
-  const int n_units = p.hdr->n_tiles * heads_here;
-  const int32_t* rec_words = reinterpret_cast<const int32_t*>(p.tiles);
-
-  // Unit fetch, two deep: wave 0 holds the atomic for the unit after next in flight and the
-  // record of the next unit in flight while the block computes the current one.
-  int32_t pend = 0, recw = 0;
-  if (wave == 0) {
-    int32_t v0 = 0;
-    if (lane == 0) v0 = atomicAdd(&p.hdr->counter[xcd], 1);
-    const int32_t u0 = __builtin_amdgcn_readfirstlane(v0);
-    if (lane == 0) pend = atomicAdd(&p.hdr->counter[xcd], 1);
-    if (lane < 16) s_rec[lane] = u0 < n_units ? rec_words[(u0 / heads_here) * 16 + lane] : 0;
-    if (lane == 0) s_next_unit = u0;
-  }
-  __syncthreads();
+  UnitQueue uq;
+  uq.init(p.hdr, p.tiles, xcd, heads_here, &s_next_unit, s_rec);
 
   // per-thread constants of the K/V tile movement
   const int ld_r = tid / C::CPR, ld_c = tid % C::CPR;
@@ -122,22 +88,12 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
   const int voff0 = ld_r * kv_row_bytes + ld_c * 16;
 
   for (;;) {
-    const int unit = __builtin_amdgcn_readfirstlane(s_next_unit);
-    if (unit >= n_units) break;
-    QTile t;
-    {
-      int32_t* tw = reinterpret_cast<int32_t*>(&t);
-#pragma unroll
-      for (int i = 0; i < 11; ++i) tw[i] = __builtin_amdgcn_readfirstlane(s_rec[i]);
-    }
+    const int unit = uq.current(&s_next_unit);
+    if (unit >= uq.n_units) break;
+    const QTile t = read_record<QTile>(s_rec);
     const int head = xcd * heads_here + unit % heads_here;
     const int kvh = head / G;
-    int32_t idx1 = 0;
-    if (wave == 0) {   // next unit's record and the following unit's number start their trips now
-      idx1 = __builtin_amdgcn_readfirstlane(pend);
-      if (lane == 0) pend = atomicAdd(&p.hdr->counter[xcd], 1);
-      recw = (lane < 16 && idx1 < n_units) ? rec_words[(idx1 / heads_here) * 16 + lane] : 0;
-    }
+    uq.prefetch();   // next unit's record and the following unit's number start their trips now
 
     const int wave_r0 = wave * 32;
     const bool wave_active = wave_r0 < t.rows;
@@ -354,12 +310,7 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         p.lse_part[(int64_t)t.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
       }
     }
-    // hand the next unit to the block
-    if (wave == 0) {
-      if (lane < 16) s_rec[lane] = recw;
-      if (lane == 0) s_next_unit = idx1;
-    }
-    __syncthreads();
+    uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block
   }
 }
 
