@@ -40,12 +40,13 @@ def _stale(out: str, deps) -> bool:
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
+    flags = FLAGS + os.environ.get("FCP_EXTRA_FLAGS", "").split()   # e.g. -DFCP_TIMING for development builds
     jobs = []
     for src in SOURCES:
         sp = os.path.join(CSRC, src)
         op = os.path.join(OBJ, os.path.splitext(src)[0] + ".o")
         if force or _stale(op, [sp] + HEADERS):
-            jobs.append([hipcc] + FLAGS + ["-c", sp, "-o", op])
+            jobs.append([hipcc] + flags + ["-c", sp, "-o", op])
 
     def run(cmd):
         if verbose:

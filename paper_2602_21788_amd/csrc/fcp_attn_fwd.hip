@@ -6,20 +6,30 @@
 // locally normalised output and LSE = ln sum exp(scaled scores).
 //
 // gfx950 design
-//   * persistent 256-thread blocks (4 wave64) pull (query tile, head) units from per-XCD
-//     counters; the tile list is sorted longest-first by the scheduler kernel;
-//   * a unit = 128 query rows of one work item for one query head; wave w owns rows
-//     32w .. 32w+31 and keeps its Q fragments in registers for the whole unit;
-//   * K/V stream through LDS in 64-key tiles, double buffered, global loads for tile t+1 in
-//     flight while tile t is computed; one barrier per tile;
+//   * persistent 512-thread blocks (8 wave64, one block per CU, two waves per SIMD) pull
+//     (query tile, head) units from per-XCD counters; the tile list is sorted longest-first by
+//     the scheduler kernel;
+//   * a unit = 128 query rows of one work item for two query heads that share a KV head (waves 0..3 take the
+//     first head, waves 4..7 the second), or, when the heads per KV head are odd, 256 query rows for one
+//     head; either way the eight waves share every K/V tile, each owns 32 rows and keeps its Q fragments
+//     in registers for the whole unit;
+//   * K and V stream through LDS in 64-key tiles filled by LDS-direct buffer loads (no register
+//     staging), four stages, chunk-permuted so that row reads (K) and transpose reads (V)
+//     run at the full LDS rate;
 //   * scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane then
 //     holds 16 keys of ONE query column, so the row maximum and sum are in-lane reductions
 //     plus a single exchange with the lane 32 away, and the exponentiated scores are already
 //     in the B-operand layout of the second contraction O^T += V^T P^T;
-//   * V^T fragments come from the row-major V tile through ds_read_b64_tr_b16 (LDS
-//     transpose read), so V is never transposed in memory;
-//   * key tiles that lie completely below the diagonal skip the mask; key tiles completely
-//     above it are never visited (the loop bound comes from the last row's position).
+//   * PING-PONG: waves w and w+4 share a SIMD (measured).  Matrix and vector instructions of
+//     DIFFERENT waves of a SIMD execute together almost perfectly, those of one wave hardly do.
+//     Each wave therefore alternates a matrix slot (scores of tile t, O^T += V^T P^T of tile t-1)
+//     with a vector slot (mask, maximum, exponentials, sum, conversion of tile t), and waves 4..7
+//     run one slot behind waves 0..3; a block barrier at every slot boundary keeps the two
+//     halves in opposite slots, so a SIMD's matrix pipe is busy in every slot;
+//   * key tiles completely below the diagonal skip the mask; key tiles completely above a
+//     wave's rows are not computed by that wave (it only keeps the barriers).
+#include <type_traits>
+
 #include "fcp_device.h"
 
 namespace fcp {
@@ -34,68 +44,104 @@ struct FwdParams {
   float* o_part;
   float* lse_part;
   int32_t tq, hq, hkv;
-  float scale_log2;  // softmax_scale * log2(e)
+  int32_t head_pair;  // 1: a unit is a 128-row tile for TWO heads of one KV head; 0: a 256-row tile for one head
+  float scale_log2;   // softmax_scale * log2(e)
 };
 
 constexpr float kRescaleThreshold = 8.f;   // log2 units
+constexpr int kFwdAhead = 4;               // LDS fragments requested this many MFMAs before their use
 
 template <int D>
 struct FwdCfg {
-  static constexpr int BM = kFwdBM;               // 128 query rows per unit (32 per wave)
+  static constexpr int BM = kFwdBM;               // 256 query rows per unit (32 per wave)
   static constexpr int BN = kFwdBN;               // 64 keys per LDS tile
-  static constexpr int KSTRIDE = D * 2 + 16;      // bytes; b128 row reads hit distinct banks
-  static constexpr int VSTRIDE = D * 2 + 64;      // bytes; 4-row transpose reads hit distinct banks
-  static constexpr int KBYTES = BN * KSTRIDE;
-  static constexpr int VBYTES = BN * VSTRIDE;
+  static constexpr int NWAVE = 8;
+  using KT = RowTile<D>;
+  using VT = TrTile<D>;
+  static constexpr int KBYTES = KT::bytes(BN);
+  static constexpr int VBYTES = VT::bytes(BN);
+  static constexpr int NSTAGE = 4;                // LDS stages of one K and one V tile
   static constexpr int STAGE = KBYTES + VBYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE;
-  static constexpr int CHUNKS = BN * D * 2 / 16;  // 16-byte pieces per tensor tile
-  static constexpr int CPT = CHUNKS / 256;        // pieces per thread
-  static constexpr int CPR = D * 2 / 16;          // pieces per row
-  static constexpr int RPP = 256 / CPR;           // rows covered by one pass of the 256 threads
+  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int RPW = BN / NWAVE;          // tile rows each wave fills
+  static constexpr int IPT = RPW / KT::RPI;       // fill instructions per wave per tile and tensor
+  static constexpr int FILLS = 2 * IPT;           // ... per tile
+  static constexpr int NKA = D == 128 ? 2 : 4;    // distinct per-lane K read addresses
+  static constexpr int NVA = D / 32;              // distinct per-lane V^T read addresses
+  static constexpr int NS = D / 16;               // MFMAs of one 32 x 32 score block
+  static constexpr int KB_STRIDE = KT::row_base(32);
+  static constexpr int kWaitFills = 0x0F70 | FILLS;   // s_waitcnt vmcnt(FILLS)
+  static_assert(RPW % KT::RPI == 0 && FILLS < 16, "fill split");
 };
 
-// On this chip plain VALU instructions do not overlap with MFMAs (measured: an MFMA plus n
-// fp32 FMAs takes the sum of both), only the transcendental unit does.  The loop therefore
-// spends as few VALU instructions per MFMA as it can: global loads go through buffer
-// instructions whose per-tile offset is a scalar (out-of-range rows read as zero, so there is
-// no clamping), LDS addresses are per-thread constants plus immediates, and the accumulator
-// rescale is lazy.
+#ifdef FCP_TIMING
+// development aid: one wave of every block adds the cycles between the marks of a step to the spare words of
+// the schedule header (0: matrix slot, 1: boundary, 2: vector slot, 3: boundary; units of 16 cycles)
+#define FCP_T(i) do { if (tid == FCP_TIMING * 64) { const long long now_ = __builtin_readcyclecounter(); if ((i) > 0) tacc[(i) - 1] += now_ - tlast; tlast = now_; } } while (0)
+#else
+#define FCP_T(i) do {} while (0)
+#endif
+
 template <int D>
-__global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
+__global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
   using C = FwdCfg<D>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  using KT = typename C::KT;
+  using VT = typename C::VT;
+  extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
   __shared__ int32_t s_next_unit;
   __shared__ int32_t s_rec[16];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;                      // 0: waves 0..3, 1: waves 4..7 (one slot behind)
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = p.hq / p.hkv;
+  const uint32_t lds0 = lds_offset(smem);
 
-  // unit numbering: with hq % 8 == 0 each XCD owns a contiguous eighth of the heads
-  const bool per_xcd = (p.hq % kNumXcd) == 0;
+  // unit numbering: when the heads split evenly each XCD owns a contiguous eighth of them (so the K/V of a
+  // KV head stay in one L2); a unit covers one head or, in head-pair mode, two consecutive heads
+  const int hpu = p.head_pair ? 2 : 1;
+  const bool per_xcd = (p.hq % (kNumXcd * hpu)) == 0;
   const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
   const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
+  const int units_per_tile = heads_here / hpu;
   UnitQueue uq;
-  uq.init(p.hdr, p.tiles, xcd, heads_here, &s_next_unit, s_rec);
+  uq.init(p.hdr, p.tiles, xcd, units_per_tile, &s_next_unit, s_rec);
 
-  // per-thread constants of the K/V tile movement
-  const int ld_r = tid / C::CPR, ld_c = tid % C::CPR;
-  const int lds_k_thread = ld_r * C::KSTRIDE + ld_c * 16;
-  const int lds_v_thread = C::KBYTES + ld_r * C::VSTRIDE + ld_c * 16;
+  // ---- per-lane constants -----------------------------------------------------------------
   const int kv_row_bytes = p.hkv * D * 2;
-  const int voff0 = ld_r * kv_row_bytes + ld_c * 16;
+  // LDS-direct fills: the lane's global offset inside a tile (K and V are permuted differently);
+  // instruction i of a wave adds i * RPI rows through the scalar offset (the permutations do not depend on i)
+  const int kfill = fill_voff<KT>(C::RPW, wave, 0, lane, kv_row_bytes);
+  const int vfill = fill_voff<VT>(C::RPW, wave, 0, lane, kv_row_bytes);
+  // K row fragments (A operand of S^T = K Q^T): lane reads tile row l32 (+32 per key block), chunk 2 ks + g2
+  int kaddr[C::NKA];
+#pragma unroll
+  for (int j = 0; j < C::NKA; ++j) kaddr[j] = tile_off<KT>(l32, 2 * j + g2);
+  // V^T fragments (A operand of O^T += V^T P^T, rows d = 32 db + l32; k-slots = keys 16 tt + {4 g2 + [0,4),
+  // 8 + 4 g2 + [0,4)}).  Transpose read: inside a 16-lane block lane i supplies the address of key row
+  // (i / 4), channels 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for key group b / 2.
+  int vaddr[C::NVA];
+  {
+    const int row0 = 4 * g2 + ((lane & 15) >> 2);
+    const int chunk0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+#pragma unroll
+    for (int db = 0; db < C::NVA; ++db) vaddr[db] = C::KBYTES + tile_off<VT>(row0, 4 * db + chunk0) + 8 * (lane & 1);
+  }
 
+#ifdef FCP_TIMING
+  long long tacc[4] = {0, 0, 0, 0}, tlast = 0;
+  const long long tstart = __builtin_readcyclecounter();
+#endif
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
     const QTile t = read_record<QTile>(s_rec);
-    const int head = xcd * heads_here + unit % heads_here;
+    const int head = xcd * heads_here + (unit % units_per_tile) * hpu + (p.head_pair ? grp : 0);
     const int kvh = head / G;
     uq.prefetch();   // next unit's record and the following unit's number start their trips now
 
-    const int wave_r0 = wave * 32;
+    const int wave_r0 = (p.head_pair ? (wave & 3) : wave) * 32;
     const bool wave_active = wave_r0 < t.rows;
     const int my_row = wave_r0 + l32;
     const bool row_valid = my_row < t.rows;
@@ -104,7 +150,64 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
     const int wave_first_pos = t.q_pos0 + wave_r0;
     const int wave_last_pos = t.q_pos0 + min(wave_r0 + 31, t.rows - 1);
 
-    // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16*ks + 8*g2 + [0,8)
+    // Key tiles of the unit: nt0 of segment 0, then nt1 of segment 1 (64 keys each, the last of a segment
+    // may be ragged).  A wave computes a prefix of them: the tiles its last row sees.
+    const int nt0 = (t.vis[0] + C::BN - 1) / C::BN, nt1 = (t.vis[1] + C::BN - 1) / C::BN;
+    const int n_iter = nt0 + nt1;
+    int n_w = 0;
+    if (wave_active) {
+      const int v0 = max(0, min(t.vis[0], wave_last_pos - t.k_pos0[0] + 1));
+      const int v1 = max(0, min(t.vis[1], wave_last_pos - t.k_pos0[1] + 1));
+      const int w0 = (v0 + C::BN - 1) / C::BN, w1 = (v1 + C::BN - 1) / C::BN;
+      n_w = w0 == nt0 ? w0 + w1 : w0;
+    }
+    // A buffer resource per segment whose extent ends with the last visible key, so rows past it
+    // arrive as zeros.
+    i32x4 rk[2], rv[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      const int64_t off = ((int64_t)t.kv_row0[s] * p.hkv + kvh) * D;
+      const int bytes = t.vis[s] > 0 ? (t.vis[s] - 1) * kv_row_bytes + D * 2 : 0;
+      rk[s] = buffer_rsrc(p.k + off, bytes);
+      rv[s] = buffer_rsrc(p.v + off, bytes);
+    }
+    // This wave's share (RPW rows of K and of V, FILLS instructions) of the LDS-direct fill of the NEXT tile in
+    // list order into the next stage (tiles are filled strictly in order 0, 1, 2, ...).  Tiles past the end of
+    // the list lie outside the resource's range, load nothing and write zeros; every call issues exactly FILLS
+    // loads, which the vmcnt waits rely on.  The running state keeps the scalar work per call small.
+    i32x4 f_rk = rk[0], f_rv = rv[0];
+    int f_left = nt0;                      // tiles left in segment 0 while it is being filled
+    bool f_seg0 = true;
+    int f_soff = 0;                        // byte offset of the next tile in its segment
+    uint32_t f_dst = lds0 + KT::row_base(C::RPW * wave);   // this wave's rows in the next stage
+    const uint32_t f_dst_end = lds0 + C::NSTAGE * C::STAGE;
+    static_assert(KT::row_base(C::RPW * 7 + KT::RPI) == KT::row_base(C::RPW * 7) + KT::row_base(KT::RPI),
+                  "a wave's rows start on a padding group boundary");
+    const uint32_t f_vdelta = C::KBYTES + VT::row_base(C::RPW * wave) - KT::row_base(C::RPW * wave);
+    auto fill_next = [&]() {
+      if (f_seg0 && f_left == 0) { f_rk = rk[1]; f_rv = rv[1]; f_seg0 = false; f_soff = 0; }   // past segment 1: out of range
+#pragma unroll
+      for (int i = 0; i < C::IPT; ++i) {
+        lds_fill_b128(f_rk, f_dst + KT::row_base(KT::RPI * i), kfill, f_soff + i * KT::RPI * kv_row_bytes);
+        lds_fill_b128(f_rv, f_dst + f_vdelta + VT::row_base(VT::RPI * i), vfill, f_soff + i * VT::RPI * kv_row_bytes);
+      }
+      --f_left;
+      f_soff += C::BN * kv_row_bytes;
+      f_dst += C::STAGE;
+      if (f_dst >= f_dst_end) f_dst -= C::NSTAGE * C::STAGE;
+    };
+    // slot boundary: this wave's fills older than its newest batch have landed, then everybody meets
+    auto boundary = [&]() {
+      __builtin_amdgcn_s_waitcnt(C::kWaitFills);
+      __syncthreads();
+    };
+
+    // Prologue fills: tiles 0 and 1.  The previous unit's last barrier guarantees that no wave still reads
+    // the stages.
+    fill_next();
+    fill_next();
+
+    // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16 ks + 8 g2 + [0,8)
     bf16x8 qf[D / 16];
     {
       const uint16_t* qp = p.q + ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
@@ -112,184 +215,136 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
       for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     }
 
-    // Key segments: a buffer resource per segment whose extent ends with the last visible key,
-    // so rows past it load as zeros.
-    const int nt0 = (t.vis[0] + C::BN - 1) / C::BN, nt1 = (t.vis[1] + C::BN - 1) / C::BN;
-    const int n_iter = nt0 + nt1;
-    __amdgpu_buffer_rsrc_t rk[2], rv[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      const int64_t off = ((int64_t)t.kv_row0[s] * p.hkv + kvh) * D;
-      const int bytes = t.vis[s] > 0 ? (t.vis[s] - 1) * kv_row_bytes + D * 2 : 0;
-      rk[s] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.k + off), (short)0, bytes, 0x00020000);
-      rv[s] = __builtin_amdgcn_make_buffer_rsrc((void*)(p.v + off), (short)0, bytes, 0x00020000);
-    }
-
     f32x16 oacc[D / 32];
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    for (int db = 0; db < D / 32; ++db) oacc[db] = zero16();
     float m_run = -INFINITY;   // running maximum in log2 units (score * scale_log2)
     float l_run = 0.f;         // this lane's share of the running sum
+    f32x16 sacc[2];            // scores of the current tile: sacc[kb][i] = key 32 kb + 8 (i/4) + 4 g2 + (i%4), query l32
+    bf16x8 pf[4];              // P^T of the current tile as B operands: k-step tt covers keys 16 tt .. 16 tt + 15
 
-    // ---- K/V tile movement ---------------------------------------------------------
-    u32x4 kreg[C::CPT], vreg[C::CPT];
-    auto issue_loads = [&](int it) {
-      const int s = it >= nt0 ? 1 : 0;
-      const int soff = (it - (s ? nt0 : 0)) * (C::BN * kv_row_bytes);
+    // ---- the two slots ------------------------------------------------------------------------
+    // K row fragment f of a tile: key block f / NS, channels 16 (f % NS) + 8 g2 + [0,8)
+    auto k_frag = [&](const int (&ka)[C::NKA], int f) -> bf16x8 {
+      const int kb = f / C::NS, ks = f % C::NS;
+      return *reinterpret_cast<const bf16x8*>(smem + ka[ks % C::NKA] + (ks / C::NKA) * (C::NKA * 32) + kb * C::KB_STRIDE);
+    };
+    // V^T fragment g: keys 16 (g / NVA) + .., channels 32 (g % NVA) + l32
+    auto v_frag = [&](const int (&va)[C::NVA], int g) -> bf16x8 {
+      const int tt = g / C::NVA, db = g % C::NVA;
+      return tr_read_8(smem + va[db] + tt * (16 * VT::row_base(1)), 8 * VT::row_base(1));
+    };
+    // Matrix slot of step `it`: scores of tile it (if DO_S), O^T += V^T P^T of tile it - 1 (if DO_PV).  The order
+    // is written out MFMA by MFMA and fenced so that every LDS fragment is requested kAhead MFMAs before the
+    // one that consumes it.
+    auto matrix_slot = [&](auto do_s_c, auto do_pv_c, int it) {
+      constexpr bool DO_S = decltype(do_s_c)::value, DO_PV = decltype(do_pv_c)::value;
+      constexpr int N1 = DO_S ? 2 * C::NS : 0, N2 = DO_PV ? 4 * C::NVA : 0, N = N1 + N2, kAhead = kFwdAhead;
+      int ka[C::NKA], va[C::NVA];
+      const int koff = (it & (C::NSTAGE - 1)) * C::STAGE, voff = ((it - 1) & (C::NSTAGE - 1)) * C::STAGE;
 #pragma unroll
-      for (int c = 0; c < C::CPT; ++c) {
-        const int voff = voff0 + c * C::RPP * kv_row_bytes;
-        if (s == 0) {
-          kreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rk[0], voff, soff, 0);
-          vreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rv[0], voff, soff, 0);
+      for (int j = 0; j < C::NKA; ++j) ka[j] = kaddr[j] + koff;
+#pragma unroll
+      for (int db = 0; db < C::NVA; ++db) va[db] = vaddr[db] + voff;
+      bf16x8 fr[N > 0 ? N : 1];
+      auto request = [&](int x) {
+        if (x < N1) fr[x] = k_frag(ka, x);
+        else if (x < N) fr[x] = v_frag(va, x - N1);
+      };
+#pragma unroll
+      for (int x = 0; x < kAhead; ++x) request(x);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int x = 0; x < N; ++x) {
+        if (x < N1) {
+          sacc[x / C::NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], qf[x % C::NS], x % C::NS == 0 ? zero16() : sacc[x / C::NS], 0, 0, 0);
         } else {
-          kreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rk[1], voff, soff, 0);
-          vreg[c] = __builtin_amdgcn_raw_buffer_load_b128(rv[1], voff, soff, 0);
+          const int g = x - N1;
+          oacc[g % C::NVA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], pf[g / C::NVA], oacc[g % C::NVA], 0, 0, 0);
         }
+        request(x + kAhead);
+        __builtin_amdgcn_sched_barrier(0);
       }
     };
-    auto store_tile = [&](int buf) {
-      unsigned char* kb = smem + buf * C::STAGE + lds_k_thread;
-      unsigned char* vb = smem + buf * C::STAGE + lds_v_thread;
-#pragma unroll
-      for (int c = 0; c < C::CPT; ++c) {
-        *reinterpret_cast<u32x4*>(kb + c * C::RPP * C::KSTRIDE) = kreg[c];
-        *reinterpret_cast<u32x4*>(vb + c * C::RPP * C::VSTRIDE) = vreg[c];
-      }
-    };
-
-    if (n_iter > 0) {
-      issue_loads(0);
-      store_tile(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; it < n_iter; ++it) {
-      const int buf = it & 1;
-      if (it + 1 < n_iter) issue_loads(it + 1);
-
+    auto tile_geom = [&](int it, int& k_pos0, int& n_valid) {
       const int s = it >= nt0 ? 1 : 0;
       const int kt = it - (s ? nt0 : 0);
-      const int k_pos0 = t.k_pos0[s] + kt * C::BN;            // position of the tile's first key
-      const int n_valid = min(C::BN, t.vis[s] - kt * C::BN);   // keys of the tile inside the segment
-      // wave-uniform: does this wave see anything in the tile / need the element mask?
-      const bool wave_sees = wave_active && k_pos0 <= wave_last_pos;
-      const bool need_mask = (k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN);
-
-      if (wave_sees) {
-        const unsigned char* kb = smem + buf * C::STAGE;
-        const unsigned char* vb = kb + C::KBYTES;
-        // LDS fragments are requested a whole group ahead of the MFMAs that use them (the
-        // sched_barriers keep the compiler from re-serialising read -> wait -> MFMA).
-        // A operand of O^T += V^T P^T: rows d = 32*db + l32; its 8 k-slots are keys
-        // 16t + {4*g2 + [0,4), 8 + 4*g2 + [0,4)}.  Transpose read: a lane supplies the address of row
-        // (l%16)/4, channels 4*(l%4) + [0,4) of its 16-lane block; block b covers channels
-        // 16*(b%2) + [0,16) for key group g2 = b/2.
-        const unsigned char* vbase = vb + (4 * g2 + ((lane & 15) >> 2)) * C::VSTRIDE +
-                                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-        auto load_vt = [&](int tt, bf16x8 (&dst)[D / 32]) {
+      k_pos0 = t.k_pos0[s] + kt * C::BN;
+      n_valid = min(C::BN, t.vis[s] - kt * C::BN);
+    };
+    // Vector slot of step `it`: mask, running maximum (lazy: raised only when some row of the wave outgrows it
+    // by 2^kRescaleThreshold, until then probabilities may exceed 1 by at most that factor), exponentials, row
+    // sum, conversion to bf16.  The row sum is taken over the unrounded fp32 values (summing the bf16-rounded
+    // ones would cost up to 2^-9 relative on a peaked row, more than the 1e-3 the LSE has to hold).
+    auto vector_slot = [&](int it) {
+      int k_pos0, n_valid;
+      tile_geom(it, k_pos0, n_valid);
+      if ((k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN)) {   // wave-uniform: causal / segment-end mask
+        const int lim = min(n_valid, q_pos - k_pos0 + 1) - 4 * g2;        // key index (minus 4 g2) below which the lane sees
 #pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            const unsigned char* a0 = vbase + (16 * tt) * C::VSTRIDE + 64 * db;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(a0));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(a0 + 8 * C::VSTRIDE));
-            dst[db] = __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi),
-                                              0, 1, 2, 3, 4, 5, 6, 7);
-          }
-        };
-        // ---- S^T[key, q] = K Q^T ------------------------------------------------------
-        f32x16 sacc[2];
-        bf16x8 ka[2][D / 16];
-        const unsigned char* krow = kb + l32 * C::KSTRIDE + 16 * g2;
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) ka[0][ks] = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks)
-          ka[1][ks] = *reinterpret_cast<const bf16x8*>(krow + 32 * C::KSTRIDE + 32 * ks);
-        {
-          const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-          sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][0], qf[0], z, 0, 0, 0);
-#pragma unroll
-          for (int ks = 1; ks < D / 16; ++ks)
-            sacc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[0][ks], qf[ks], sacc[0], 0, 0, 0);
-          __builtin_amdgcn_sched_barrier(0);
-          sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[1][0], qf[0], z, 0, 0, 0);
-#pragma unroll
-          for (int ks = 1; ks < D / 16; ++ks)
-            sacc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[1][ks], qf[ks], sacc[1], 0, 0, 0);
-        }
-        bf16x8 vt0[D / 32], vt1[D / 32];
-        load_vt(0, vt0);     // lands while the scores are exponentiated
-        load_vt(1, vt1);
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- mask + online softmax ------------------------------------------------------
-        // register i of block kbk is key 32*kbk + 8*(i/4) + 4*g2 + (i%4) of the tile
-        if (need_mask) {
-#pragma unroll
-          for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const int kk = 32 * kbk + 8 * (i / 4) + 4 * g2 + (i % 4);
-              if (kk >= n_valid || k_pos0 + kk > q_pos) sacc[kbk][i] = -INFINITY;
-            }
-        }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kbk][i]);
-        mx = lane32_partner_max(mx) * p.scale_log2;
-        // Lazy rescale: the running maximum is raised only when some row of the wave outgrows it by
-        // 2^kRescaleThreshold; until then probabilities may exceed 1 (by at most that factor).
-        if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleThreshold) != 0) {
-          const float m_new = fmaxf(m_run, mx);
-          const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
-          m_run = m_new;
-          l_run *= alpha;
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-        }
-        const float m_use = m_run == -INFINITY ? 0.f : m_run;
-        float psum = 0.f;
-        bf16x8 pf[4];   // P^T as B operand: k-step t covers keys 16t..16t+15 of the tile
-        // the row sum is taken over the unrounded fp32 values: summing the bf16-rounded ones
-        // (v_dot2c) would halve the adds but costs up to 2^-9 relative on a peaked row, i.e.
-        // more than the 1e-3 the LSE has to hold
-#pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float e = __builtin_amdgcn_exp2f(fmaf(sacc[kbk][i], p.scale_log2, -m_use));
-            psum += e;
-            pf[2 * kbk + i / 8][i % 8] = (__bf16)e;
-          }
-        l_run += psum;
-        __builtin_amdgcn_sched_barrier(0);
-        // ---- O^T[d, q] += V^T P^T ---------------------------------------------------------
-        bf16x8 vt2[D / 32], vt3[D / 32];
-        load_vt(2, vt2);
-        load_vt(3, vt3);
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt0[db], pf[0], oacc[db], 0, 0, 0);
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt1[db], pf[1], oacc[db], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt2[db], pf[2], oacc[db], 0, 0, 0);
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db) oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt3[db], pf[3], oacc[db], 0, 0, 0);
+          for (int i = 0; i < 16; ++i)
+            if (32 * kb + 8 * (i / 4) + (i % 4) >= lim) sacc[kb][i] = -INFINITY;
       }
+      float mx = max3(sacc[0][0], sacc[0][1], sacc[1][0]);
+      mx = fmaxf(mx, sacc[1][1]);
+#pragma unroll
+      for (int i = 2; i < 16; i += 2) mx = max3(max3(mx, sacc[0][i], sacc[0][i + 1]), sacc[1][i], sacc[1][i + 1]);
+      mx = lane32_partner_max(mx) * p.scale_log2;
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + kRescaleThreshold) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+      }
+      const float m_use = m_run == -INFINITY ? 0.f : m_run;
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 32; e += 2) {
+        const float e0 = __builtin_amdgcn_exp2f(fmaf(sacc[e / 16][e % 16], p.scale_log2, -m_use));
+        const float e1 = __builtin_amdgcn_exp2f(fmaf(sacc[e / 16][e % 16 + 1], p.scale_log2, -m_use));
+        psum += e0;
+        psum += e1;
+        pf[e / 8][e % 8] = (__bf16)e0;
+        pf[e / 8][e % 8 + 1] = (__bf16)e1;
+      }
+      l_run += psum;
+    };
 
-      if (it + 1 < n_iter) store_tile(buf ^ 1);
-      __syncthreads();
+    // ---- the unit -------------------------------------------------------------------------------
+    // Step `it` of a wave = matrix slot (fills of tile it+2; scores of tile it; second contraction of tile it-1)
+    // then vector slot (tile it).  Waves 4..7 start one slot late.  A fill overwrites stage (it+2) % 4, whose
+    // previous tile it-2 was last read in matrix slot it-1 of the late waves, which ended before this slot.
+    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __syncthreads();                       // tiles 0 and 1 have landed
+    if (grp == 1) __syncthreads();
+    using T = std::true_type;
+    using F = std::false_type;
+    for (int it = 0; it <= n_iter; ++it) {
+      FCP_T(0);
+      fill_next();
+      FCP_T(1);
+      const bool do_s = it < n_w, do_pv = it > 0 && it - 1 < n_w;
+      // the matrix stream goes first at the SIMD's issue port: an MFMA is wanted every 32 cycles and must not
+      // queue behind the partner wave's vector instructions
+      __builtin_amdgcn_s_setprio(3);
+      if (do_s && do_pv) matrix_slot(T{}, T{}, it);
+      else if (do_s) matrix_slot(T{}, F{}, it);
+      else if (do_pv) matrix_slot(F{}, T{}, it);
+      __builtin_amdgcn_s_setprio(0);
+      FCP_T(2);
+      boundary();
+      if (do_s) vector_slot(it);
+      FCP_T(3);
+      boundary();
+      FCP_T(4);
     }
+    if (grp == 0) __syncthreads();
 
     // ---- epilogue: normalise, write partial O (fp32) and LSE --------------------------------
     const float l_tot = lane32_partner_sum(l_run);
@@ -310,8 +365,14 @@ __global__ __launch_bounds__(256, 2) void fwd_kernel(const FwdParams p) {
         p.lse_part[(int64_t)t.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
       }
     }
-    uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block
+    uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block (barrier: LDS stages are free)
   }
+#ifdef FCP_TIMING
+  if (tid == FCP_TIMING * 64) {
+    for (int i = 0; i < 4; ++i) atomicAdd(&p.hdr->pad1[i], (int32_t)(tacc[i] >> 4));
+    atomicAdd(&p.hdr->pad0, (int32_t)((__builtin_readcyclecounter() - tstart) >> 8));
+  }
+#endif
 }
 
 }  // namespace
@@ -346,7 +407,9 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap = fcp::q_tile_cap(tq, tkv, n_work, n_parts);
   if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
-  int rc = fcp::launch_schedule(false, fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
+  // two heads of one KV head per unit when the heads pair up, else twice the rows for one head
+  const int head_pair = ((hq / hkv) % 2 == 0) ? 1 : 0;
+  int rc = fcp::launch_schedule(false, head_pair ? fcp::kFwdBM / 2 : fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
                                 lse_part, (int64_t)n_parts * hq * tq, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
@@ -357,31 +420,31 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   p.tiles = fcp::sched_tiles(scratch, n_work);
   p.o_part = o_part; p.lse_part = lse_part;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
+  p.head_pair = head_pair;
   p.scale_log2 = softmax_scale * 1.4426950408889634f;
 
   int dev = 0, n_cu = 256;
   FCP_HIP_CHECK(hipGetDevice(&dev));
   FCP_HIP_CHECK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
-  int64_t units = cap * hq;
-  int64_t blocks = (int64_t)n_cu * 2;
+  int64_t units = cap * (hq / (head_pair ? 2 : 1));
+  int64_t blocks = n_cu;                               // one 512-thread block per CU
   if (blocks > units) blocks = (units + 7) / 8 * 8;   // keep a multiple of the XCD count
   if (blocks < 8) blocks = 8;
+  static bool attr_done[2] = {false, false};
   if (head_dim == 128) {
-    static bool attr_done = false;
-    if (!attr_done) {
+    if (!attr_done[0]) {
       FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::fwd_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                         fcp::FwdCfg<128>::LDS_BYTES));
-      attr_done = true;
+      attr_done[0] = true;
     }
-    hipLaunchKernelGGL(fcp::fwd_kernel<128>, dim3((unsigned)blocks), dim3(256), fcp::FwdCfg<128>::LDS_BYTES, st, p);
+    hipLaunchKernelGGL(fcp::fwd_kernel<128>, dim3((unsigned)blocks), dim3(512), fcp::FwdCfg<128>::LDS_BYTES, st, p);
   } else {
-    static bool attr_done = false;
-    if (!attr_done) {
+    if (!attr_done[1]) {
       FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::fwd_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                         fcp::FwdCfg<64>::LDS_BYTES));
-      attr_done = true;
+      attr_done[1] = true;
     }
-    hipLaunchKernelGGL(fcp::fwd_kernel<64>, dim3((unsigned)blocks), dim3(256), fcp::FwdCfg<64>::LDS_BYTES, st, p);
+    hipLaunchKernelGGL(fcp::fwd_kernel<64>, dim3((unsigned)blocks), dim3(512), fcp::FwdCfg<64>::LDS_BYTES, st, p);
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;

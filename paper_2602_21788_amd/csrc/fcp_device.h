@@ -36,10 +36,91 @@ __device__ inline float lane32_partner_sum(float x) {
   return __int_as_float(r[0]) + __int_as_float(r[1]);
 }
 
+// Maximum of three as one v_maximum3_f32 (IEEE-754-2019 maximum: no NaN-quieting moves of the inputs,
+// which fmaxf brings in IEEE mode).
+__device__ inline float max3(float a, float b, float c) {
+  return __builtin_elementwise_maximum(__builtin_elementwise_maximum(a, b), c);
+}
+
 __device__ inline f32x16 zero16() {
   const f32x16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   return z;
 }
+
+// ---- LDS tiles filled by LDS-direct buffer loads ----------------------------------------------
+// A wave-wide buffer_load_dwordx4 ... lds puts lane L's 16 bytes at (M0 base) + 16 L (verified on the
+// chip; lanes whose address is out of the resource's range write zeros), so a tile row cannot be
+// padded.  Bank conflicts are avoided by permuting the 16-byte chunks of a row instead: chunk c of
+// tile row r is stored at chunk position c ^ key(r).  Two layouts, both read at the full 256 B/clk:
+//   RowTile  rows are read whole as MFMA operands (ds_read_b128, 16 consecutive rows per clock);
+//   TrTile   4-row x 64-byte blocks are read with ds_read_b64_tr_b16 (32 lanes per clock).
+// s_waitcnt immediate: vmcnt(0) (bits 3:0 and 15:14), expcnt and lgkmcnt left at their maxima.  A
+// workgroup barrier does not wait for a wave's outstanding LDS-direct loads by itself.
+constexpr int kWaitVm0 = 0x0F70;
+#define FCP_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer resource: base address, no stride, `bytes` addressable bytes (accesses past them read as
+// zero), 32-bit untyped data format.
+__device__ inline i32x4 buffer_rsrc(const void* base, int bytes) {
+  const uint64_t a = reinterpret_cast<uint64_t>(base);
+  const i32x4 r = {(int)(uint32_t)a, (int)((a >> 32) & 0xffffu), bytes, 0x00020000};
+  return r;
+}
+
+// LDS byte offset of a __shared__ object (what M0 and the ds instructions take).
+__device__ inline uint32_t lds_offset(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
+}
+
+// One wave-wide LDS-direct load: lane L's 16 bytes from rsrc[voff + soff] land at LDS offset lds + 16 L.
+// Written in assembly so that the compiler does not count it among the LDS stores it orders LDS reads
+// after (it would make the wave wait for the load just issued before its next LDS read); the caller waits
+// with s_waitcnt vmcnt and a barrier before anybody reads the tile.  `lds` and `soff` must be wave-uniform.
+// M0 is not used by anything else in these kernels.
+__device__ inline void lds_fill_b128(i32x4 rsrc, uint32_t lds, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
+template <int D>
+struct RowTile {
+  static constexpr int CPR = D / 8;        // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;     // rows one wave-wide load instruction fills
+  // D = 128: 64 bytes of padding after every 4 rows (one load instruction) + the row's low two bits;
+  // D = 64: two rows share a 256-byte bank cycle, so row/2 permutes all 8 chunks.
+  __host__ __device__ static constexpr int row_base(int row) { return D == 128 ? row * 256 + (row >> 2) * 64 : row * 128; }
+  __host__ __device__ static constexpr int key(int row) { return D == 128 ? (row & 3) : ((row >> 1) & 7); }
+  __host__ __device__ static constexpr int bytes(int rows) { return row_base(rows); }
+};
+
+template <int D>
+struct TrTile {
+  static constexpr int CPR = D / 8;
+  static constexpr int RPI = 64 / CPR;
+  __host__ __device__ static constexpr int row_base(int row) { return row * D * 2; }
+  __host__ __device__ static constexpr int key(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+  __host__ __device__ static constexpr int bytes(int rows) { return rows * D * 2; }
+};
+
+// Byte offset of chunk c of row `row` inside a tile.
+template <typename T>
+__device__ inline int tile_off(int row, int c) { return T::row_base(row) + ((c ^ T::key(row)) << 4); }
+
+// Per-lane part of the global offset for the LDS-direct fill of a tile by several waves: wave w fills
+// tile rows rpw * w .. rpw * w + rpw - 1 with rpw / RPI instructions; in instruction i the lane
+// supplies row (lane / CPR) of the RPI rows and the chunk that belongs at chunk position lane % CPR.
+template <typename T>
+__device__ inline int fill_voff(int rpw, int wave, int i, int lane, int row_bytes) {
+  const int row = rpw * wave + T::RPI * i + lane / T::CPR;
+  return row * row_bytes + (((lane % T::CPR) ^ T::key(row)) << 4);
+}
+
+// Scheduling groups (llvm.amdgcn.sched.group.barrier): the next `n` instructions of class `mask` in
+// the issue order of the enclosing basic block.
+constexpr int kSgValu = 0x002, kSgMfma = 0x008, kSgDsRead = 0x100, kSgDsWrite = 0x200, kSgVmemRead = 0x020;
+#define sched_group(mask, n) __builtin_amdgcn_sched_group_barrier((mask), (n), 0)
 
 // Unit queue of a persistent block.  Units are numbered per XCD counter; unit u of an XCD is
 // (tile u / per_tile, sub-index u % per_tile).  Wave 0 keeps the atomic for the unit after next

@@ -56,7 +56,7 @@ struct KTile {                   // a block of keys of one segment of one work i
 static_assert(sizeof(QTile) == 64 && sizeof(KTile) == 64, "tile records are 16 words");
 struct Tile { int32_t w[16]; };  // storage type of the list
 
-constexpr int kFwdBM = 128;      // query rows per forward unit
+constexpr int kFwdBM = 256;      // query rows per forward unit
 constexpr int kFwdBN = 64;       // keys per forward inner step
 constexpr int kDqBM = 128;       // query rows per dQ unit
 constexpr int kDqBN = 64;        // keys per dQ inner step

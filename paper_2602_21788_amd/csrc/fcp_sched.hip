@@ -272,6 +272,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     hdr->n_rejected = s_rej;
     hdr->max_cost = s_max;
     hdr->pad0 = 0;
+    for (int c = 0; c < 4; ++c) hdr->pad1[c] = 0;
     for (int c = 0; c < kNumXcd; ++c) hdr->counter[c] = 0;
   }
 }
