@@ -23,281 +23,10 @@
 // Both add their result to the caller's fp32 accumulators once per unit: with plain
 // load-add-store when the scheduler found that no other item of the launch touches the same
 // rows (always the case for degree-1 sequences), otherwise with fp32 atomics.
-#include "fcp_internal.h"
+#include "fcp_bwd.h"
 
 namespace fcp {
 namespace {
-
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-struct BwdParams {
-  const uint16_t* q;
-  const uint16_t* k;
-  const uint16_t* v;
-  const uint16_t* d_o;
-  const float* lse;
-  const float* delta;
-  const int32_t* cu;
-  const fcp_work_desc* work;
-  SchedHeader* hdr;          // schedule region of this kernel
-  const int32_t* flags;
-  const Tile* tiles;
-  float* dq;
-  float* dk;
-  float* dv;
-  int32_t tq, hq, hkv;
-  float scale, scale_log2;
-};
-
-constexpr float kLog2e = 1.4426950408889634f;
-
-__device__ inline bf16x8 tr_read_8(const unsigned char* p0, int second_off) {
-  // two 4-row LDS transpose reads -> the 8 k-slots of one MFMA operand
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0 + second_off));
-  return __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-__device__ inline f32x16 zero16() {
-  f32x16 z;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) z[i] = 0.f;
-  return z;
-}
-
-// ============================================================================================
-// dK / dV
-// ============================================================================================
-template <int D>
-struct DkvCfg {
-  static constexpr int BN = kBwdBN;                // 128 keys per unit
-  static constexpr int BM = kBwdBM;                // 32 query rows per inner step
-  static constexpr int RSTRIDE = D * 2 + 32;       // Q/dO rows in LDS: compromise between b128 row reads
-                                                   // and 4-row transpose reads (measured)
-  static constexpr int QBYTES = BM * RSTRIDE;
-  static constexpr int STAT_BYTES = 2 * BM * 4;    // LSE (log2 units) and delta of the block
-  static constexpr int STAGE = 2 * QBYTES + STAT_BYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE;
-  static constexpr int CPR = D * 2 / 16;           // 16-byte pieces per row
-  static constexpr int QPT = BM * CPR / 256;       // pieces per thread per tensor
-};
-
-template <int D>
-__global__ __launch_bounds__(256, 1) void dkv_kernel(const BwdParams p) {
-  using C = DkvCfg<D>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int32_t s_unit;
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, g2 = lane >> 5;
-  const int G = p.hq / p.hkv;
-  const bool per_xcd = (p.hkv % kNumXcd) == 0;
-  const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
-  const int kvh_here = per_xcd ? p.hkv / kNumXcd : p.hkv;
-  const int n_units = p.hdr->n_tiles * kvh_here;
-  const int tr_row = (lane & 15) >> 2;
-  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-  for (;;) {
-    if (tid == 0) s_unit = atomicAdd(&p.hdr->counter[xcd], 1);
-    __syncthreads();
-    const int unit = __builtin_amdgcn_readfirstlane(s_unit);
-    __syncthreads();
-    if (unit >= n_units) break;
-    const int tile_i = unit / kvh_here;
-    const int kvh = xcd * kvh_here + unit % kvh_here;
-    const KTile t = *reinterpret_cast<const KTile*>(&p.tiles[tile_i]);
-    struct { int32_t q_local_off, q_seq_start, q_len; } w = {t.q_local_off, t.q_seq_start, t.q_len};
-    const bool exclusive = (t.flags & kFlagSeg0Exclusive) != 0;
-    const int n_keys = t.n_keys;                               // >= 1 by construction
-    const int k_pos0 = t.k_pos0;
-    const int64_t kv_row0 = t.kv_row0;
-    const int my_key = 32 * wave + l32;
-    const int my_key_ld = min(my_key, n_keys - 1);
-    const int my_k_pos = k_pos0 + my_key;
-    const bool my_key_valid = my_key < n_keys;
-
-    const int first_row = max(0, k_pos0 - w.q_seq_start);
-    const int qb0 = first_row / C::BM;
-    const int nqb = (w.q_len + C::BM - 1) / C::BM - qb0;       // query blocks per head, >= 1
-    const int n_iter = nqb * G;
-
-    // own-key fragments: B operands of S = Q K^T and dP = dO V^T (lane = key column)
-    bf16x8 kf[D / 16], vf[D / 16];
-    {
-      const int64_t off = ((kv_row0 + my_key_ld) * p.hkv + kvh) * D + 8 * g2;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        kf[ks] = *reinterpret_cast<const bf16x8*>(p.k + off + 16 * ks);
-        vf[ks] = *reinterpret_cast<const bf16x8*>(p.v + off + 16 * ks);
-      }
-    }
-
-    u32x4 qreg[C::QPT], doreg[C::QPT];
-    float statreg = 0.f;
-    auto issue_loads = [&](int it) {
-      const int head = kvh * G + it / nqb;
-      const int qb = qb0 + it % nqb;
-#pragma unroll
-      for (int c = 0; c < C::QPT; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        const int row = min(qb * C::BM + r, w.q_len - 1);
-        const int64_t off = ((int64_t)(w.q_local_off + row) * p.hq + head) * D + col * 8;
-        qreg[c] = *reinterpret_cast<const u32x4*>(p.q + off);
-        doreg[c] = *reinterpret_cast<const u32x4*>(p.d_o + off);
-      }
-      if (tid < 2 * C::BM) {
-        const int r = tid & (C::BM - 1);
-        const int row = min(qb * C::BM + r, w.q_len - 1);
-        const int64_t off = (int64_t)head * p.tq + w.q_local_off + row;
-        if (tid < C::BM) {
-          const float l = p.lse[off];
-          statreg = l == -INFINITY ? INFINITY : l * kLog2e;   // a row without keys contributes nothing
-        } else {
-          statreg = p.delta[off];
-        }
-      }
-    };
-    auto store_stage = [&](int buf) {
-      unsigned char* qs = smem + buf * C::STAGE;
-      unsigned char* dos = qs + C::QBYTES;
-#pragma unroll
-      for (int c = 0; c < C::QPT; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        *reinterpret_cast<u32x4*>(qs + r * C::RSTRIDE + col * 16) = qreg[c];
-        *reinterpret_cast<u32x4*>(dos + r * C::RSTRIDE + col * 16) = doreg[c];
-      }
-      if (tid < 2 * C::BM) reinterpret_cast<float*>(dos + C::QBYTES)[tid] = statreg;
-    };
-
-    issue_loads(0);
-    store_stage(0);
-    __syncthreads();
-
-    f32x16 dvacc[D / 32], dkacc[D / 32];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) { dvacc[db] = zero16(); dkacc[db] = zero16(); }
-
-    for (int it = 0; it < n_iter; ++it) {
-      const int buf = it & 1;
-      if (it + 1 < n_iter) issue_loads(it + 1);
-      const unsigned char* qs = smem + buf * C::STAGE;
-      const unsigned char* dos = qs + C::QBYTES;
-      const float* stat = reinterpret_cast<const float*>(dos + C::QBYTES);
-
-      const int qb = qb0 + it % nqb;
-      const int row0 = qb * C::BM;
-      const int q_pos0 = w.q_seq_start + row0;
-      const int rows_here = min(C::BM, w.q_len - row0);
-      const bool need_mask = (k_pos0 + 32 * wave + 31 > q_pos0) || (32 * wave + 32 > n_keys) || (rows_here < C::BM);
-
-      {
-        // Phase 1: all row fragments of the block are requested before the first MFMA, so the
-        // LDS latency is paid once and not once per MFMA.
-        bf16x8 aq[D / 16], ado[D / 16];
-        const unsigned char* qrow = qs + l32 * C::RSTRIDE + 16 * g2;
-        const unsigned char* dorow = dos + l32 * C::RSTRIDE + 16 * g2;
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
-          aq[ks] = *reinterpret_cast<const bf16x8*>(qrow + 32 * ks);
-          ado[ks] = *reinterpret_cast<const bf16x8*>(dorow + 32 * ks);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // Phase 2: S = Q K^T, dP = dO V^T  [32 rows x 32 own keys]
-        f32x16 sacc = zero16(), dpacc = zero16();
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[ks], kf[ks], sacc, 0, 0, 0);
-          dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ado[ks], vf[ks], dpacc, 0, 0, 0);
-        }
-        // Phase 3: transposed fragments for the second pair of contractions and the row
-        // statistics are requested now; they arrive while the MFMAs above drain and the
-        // exponentials below run.
-        bf16x8 tdo[2][D / 32], tq[2][D / 32];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            const int roff = (16 * t + 4 * g2 + tr_row) * C::RSTRIDE + (32 * db + tr_col) * 2;
-            tdo[t][db] = tr_read_8(dos + roff, 8 * C::RSTRIDE);
-            tq[t][db] = tr_read_8(qs + roff, 8 * C::RSTRIDE);
-          }
-        f32x4 lse4[4], del4[4];
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          lse4[r4] = *reinterpret_cast<const f32x4*>(stat + 8 * r4 + 4 * g2);
-          del4[r4] = *reinterpret_cast<const f32x4*>(stat + C::BM + 8 * r4 + 4 * g2);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // Phase 4: P = exp2(c s - LSE2), dS = P (dP - delta); register i is query row
-        // 8*(i/4) + 4*g2 + i%4 of the block
-        bf16x8 pb[2], dsb[2];
-        if (need_mask) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int r = 8 * (i / 4) + 4 * g2 + (i % 4);
-            float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, -lse4[i / 4][i % 4]));
-            if (!my_key_valid || r >= rows_here || my_k_pos > q_pos0 + r) pr = 0.f;
-            pb[i / 8][i % 8] = (__bf16)pr;
-            dsb[i / 8][i % 8] = (__bf16)(pr * (dpacc[i] - del4[i / 4][i % 4]));
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float pr = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, -lse4[i / 4][i % 4]));
-            pb[i / 8][i % 8] = (__bf16)pr;
-            dsb[i / 8][i % 8] = (__bf16)(pr * (dpacc[i] - del4[i / 4][i % 4]));
-          }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        // Phase 5: dV^T += dO^T P, dK^T += Q^T dS.  k-slots of step t are rows 16t + 4*g2 + [0,4)
-        // and 16t + 8 + 4*g2 + [0,4), matching pb/dsb
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            dvacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tdo[t][db], pb[t], dvacc[db], 0, 0, 0);
-            dkacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tq[t][db], dsb[t], dkacc[db], 0, 0, 0);
-          }
-      }
-      if (it + 1 < n_iter) store_stage(buf ^ 1);
-      __syncthreads();
-    }
-
-    // epilogue: dK^T, dV^T [channel x own key] -> pool accumulators
-    if (my_key_valid) {
-      float* dvp = p.dv + ((kv_row0 + my_key) * p.hkv + kvh) * D + 4 * g2;
-      float* dkp = p.dk + ((kv_row0 + my_key) * p.hkv + kvh) * D + 4 * g2;
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int c = 32 * db + 8 * r4;
-          if (exclusive) {
-            f32x4 a = *reinterpret_cast<f32x4*>(dvp + c), b = *reinterpret_cast<f32x4*>(dkp + c);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { a[e] += dvacc[db][4 * r4 + e]; b[e] += dkacc[db][4 * r4 + e] * p.scale; }
-            *reinterpret_cast<f32x4*>(dvp + c) = a;
-            *reinterpret_cast<f32x4*>(dkp + c) = b;
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              unsafeAtomicAdd(dvp + c + e, dvacc[db][4 * r4 + e]);
-              unsafeAtomicAdd(dkp + c + e, dkacc[db][4 * r4 + e] * p.scale);
-            }
-          }
-        }
-    }
-  }
-}
 
 // ============================================================================================
 // dQ
@@ -537,21 +266,25 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   const size_t need = fcp_scratch_bytes(FCP_SCRATCH_BWD, tq, tkv, hq, hkv, head_dim, n_work, 1);
   if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_bwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
 
+  if ((int64_t)tq * hq * head_dim * 2 >= ((int64_t)1 << 31))
+    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim * 2 must stay below 2^31 bytes");
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap_kv = fcp::kv_tile_cap(tkv, n_work);
   const int64_t cap_q = fcp::q_tile_cap(tq, tkv, n_work, 1 << 20);
   if (cap_kv > INT32_MAX / 64 || cap_q > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: too many tiles");
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
+  float* stats = reinterpret_cast<float*>(static_cast<char*>(region_q) + fcp::sched_region_bytes(n_work, cap_q));
   int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
   rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
+  if ((rc = fcp::launch_row_stats(lse, delta, (int64_t)hq * tq, stats, st)) != FCP_OK) return rc;
 
   fcp::BwdParams p;
   p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v; p.d_o = (const uint16_t*)d_o;
-  p.lse = lse; p.delta = delta; p.cu = cu_seqlens_kv; p.work = work;
+  p.lse = lse; p.delta = delta; p.stats = stats;
   p.dq = dq_acc; p.dk = dk_acc; p.dv = dv_acc;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.scale = softmax_scale; p.scale_log2 = softmax_scale * fcp::kLog2e;
@@ -568,22 +301,11 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
 
   // dK/dV over key tiles
   p.hdr = (fcp::SchedHeader*)region_kv;
-  p.flags = fcp::sched_flags(region_kv, n_work);
   p.tiles = fcp::sched_tiles(region_kv, n_work);
-  if (head_dim == 128) {
-    static bool done = false;
-    if ((rc = fcp::set_lds_once(fcp::dkv_kernel<128>, fcp::DkvCfg<128>::LDS_BYTES, &done)) != FCP_OK) return rc;
-    hipLaunchKernelGGL(fcp::dkv_kernel<128>, grid_for(cap_kv * hkv, 1), dim3(256), fcp::DkvCfg<128>::LDS_BYTES, st, p);
-  } else {
-    static bool done = false;
-    if ((rc = fcp::set_lds_once(fcp::dkv_kernel<64>, fcp::DkvCfg<64>::LDS_BYTES, &done)) != FCP_OK) return rc;
-    hipLaunchKernelGGL(fcp::dkv_kernel<64>, grid_for(cap_kv * hkv, 1), dim3(256), fcp::DkvCfg<64>::LDS_BYTES, st, p);
-  }
-  FCP_HIP_CHECK(hipGetLastError());
+  if ((rc = fcp::launch_dkv(p, head_dim, cap_kv * hkv, n_cu, st)) != FCP_OK) return rc;
 
   // dQ over query tiles
   p.hdr = (fcp::SchedHeader*)region_q;
-  p.flags = fcp::sched_flags(region_q, n_work);
   p.tiles = fcp::sched_tiles(region_q, n_work);
   if (head_dim == 128) {
     static bool done = false;

@@ -1,0 +1,30 @@
+// Declarations shared by the two backward kernels' translation units (not installed).
+#pragma once
+#include "fcp_device.h"
+
+namespace fcp {
+
+struct BwdParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  const uint16_t* d_o;
+  const float* lse;
+  const float* delta;
+  const float* stats;        // two planes [hq][tq]: -LSE * log2 e (-inf for a row without keys), then -delta
+  SchedHeader* hdr;          // schedule region of the kernel being launched
+  const Tile* tiles;
+  float* dq;
+  float* dk;
+  float* dv;
+  int32_t tq, hq, hkv;
+  float scale, scale_log2;
+};
+
+// Row statistics in the form the backward kernels consume, written once per backward step.
+int launch_row_stats(const float* lse, const float* delta, int64_t n, float* stats, hipStream_t stream);
+
+// dK / dV over key tiles (csrc/fcp_attn_dkv.hip).  `units` = upper bound of (key tile, KV head) units.
+int launch_dkv(const BwdParams& p, int head_dim, int64_t units, int n_cu, hipStream_t stream);
+
+}  // namespace fcp

@@ -25,6 +25,13 @@ __device__ inline bf16x8 tr_read_8(const unsigned char* p0, int second_off) {
   return __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Same with the two 4-row reads at unrelated addresses (chunk-permuted tiles).
+__device__ inline bf16x8 tr_read_8(const unsigned char* p_lo, const unsigned char* p_hi) {
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p_lo));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p_hi));
+  return __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // v_permlane32_swap exchanges the upper half of the first operand with the lower half of the
 // second; with both operands = x every lane ends up holding x of lanes l and l^32.
 __device__ inline float lane32_partner_max(float x) {
@@ -104,6 +111,37 @@ struct TrTile {
   __host__ __device__ static constexpr int bytes(int rows) { return rows * D * 2; }
 };
 
+// Rows read BOTH whole (ds_read_b128) and through ds_read_b64_tr_b16: the key permutes all chunk bits.
+template <int D>
+struct DualTile {
+  static constexpr int CPR = D / 8;
+  static constexpr int RPI = 64 / CPR;
+  __host__ __device__ static constexpr int row_base(int row) { return row * D * 2; }
+  // D = 128: the two 2-bit fields of row % 16 swapped (row reads need 16 rows apart in all four bits, transpose
+  // reads need 4 consecutive rows apart in the upper two); D = 64: two rows per 256-byte bank cycle, so row / 2
+  // (3 bits) permutes the 8 chunks, its lowest bit going to the top.
+  __host__ __device__ static constexpr int key(int row) {
+    return D == 128 ? (((row & 3) << 2) | ((row >> 2) & 3)) : (((((row >> 1) & 7) & 1) << 2) | (((row >> 1) & 7) >> 1));
+  }
+  __host__ __device__ static constexpr int bytes(int rows) { return rows * D * 2; }
+};
+
+// acc += A B (v_mfma_f32_32x32x16_bf16) with the accumulator held in ACCUMULATION registers (AGPRs): long-lived
+// accumulators stay out of the vector register file.  The compiler does not know that this is a matrix
+// instruction, so two hazards are the caller's: at least two other MFMAs (or mfma_settle) between two MFMAs
+// on the same accumulator, and mfma_settle() before anything else reads or writes an accumulator just written.
+__device__ inline void mfma_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
+  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// 20 wait states: more than the 8 passes + 2 of the matrix instruction above.
+__device__ inline void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
+
+// One wave-wide LDS-direct load of one dword per lane: lane L's 4 bytes land at LDS offset lds + 4 L.
+__device__ inline void lds_fill_b32(i32x4 rsrc, uint32_t lds, int voff, int soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+               :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
 // Byte offset of chunk c of row `row` inside a tile.
 template <typename T>
 __device__ inline int tile_off(int row, int c) { return T::row_base(row) + ((c ^ T::key(row)) << 4); }
@@ -121,6 +159,35 @@ __device__ inline int fill_voff(int rpw, int wave, int i, int lane, int row_byte
 // the issue order of the enclosing basic block.
 constexpr int kSgValu = 0x002, kSgMfma = 0x008, kSgDsRead = 0x100, kSgDsWrite = 0x200, kSgVmemRead = 0x020;
 #define sched_group(mask, n) __builtin_amdgcn_sched_group_barrier((mask), (n), 0)
+
+// Development aid (compiled in with -DFCP_TIMING=<wave>): that wave of every block accumulates the shader
+// cycles between consecutive marks i-1 -> i (i = 1..4) and adds them, in units of 16 cycles, to the four spare
+// words of the schedule header at kernel end (word pad0: whole kernel, units of 256 cycles).
+#ifdef FCP_TIMING
+struct PhaseTimer {
+  long long acc[4] = {0, 0, 0, 0}, last = 0, start = 0;
+  __device__ void begin() { start = __builtin_readcyclecounter(); }
+  __device__ void mark(int i) {
+    if (threadIdx.x == FCP_TIMING * 64) {
+      const long long now = __builtin_readcyclecounter();
+      if (i > 0) acc[i - 1] += now - last;
+      last = now;
+    }
+  }
+  __device__ void end(SchedHeader* hdr) {
+    if (threadIdx.x == FCP_TIMING * 64) {
+      for (int i = 0; i < 4; ++i) atomicAdd(&hdr->pad1[i], (int32_t)(acc[i] >> 4));
+      atomicAdd(&hdr->pad0, (int32_t)((__builtin_readcyclecounter() - start) >> 8));
+    }
+  }
+};
+#else
+struct PhaseTimer {
+  __device__ void begin() {}
+  __device__ void mark(int) {}
+  __device__ void end(SchedHeader*) {}
+};
+#endif
 
 // Unit queue of a persistent block.  Units are numbered per XCD counter; unit u of an XCD is
 // (tile u / per_tile, sub-index u % per_tile).  Wave 0 keeps the atomic for the unit after next

@@ -317,11 +317,12 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
 
 extern "C" size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t hq, int32_t hkv,
                                     int32_t head_dim, int64_t n_work, int32_t n_parts) {
-  (void)hq; (void)hkv; (void)head_dim;
+  (void)hkv; (void)head_dim;
   if (tq < 0 || tkv < 0 || n_work < 0 || n_parts < 0) return 0;
-  if (which == FCP_SCRATCH_BWD)   // key-tile list (dK/dV kernel) followed by query-tile list (dQ kernel)
+  if (which == FCP_SCRATCH_BWD)   // key-tile list (dK/dV kernel), query-tile list (dQ kernel), packed row statistics
     return fcp::sched_region_bytes(n_work, fcp::kv_tile_cap(tkv, n_work)) +
-           fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, 1 << 20));
+           fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, 1 << 20)) +
+           fcp::pad_to((size_t)hq * (size_t)tq * 8, 256);
   return fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, n_parts));
 }
 
