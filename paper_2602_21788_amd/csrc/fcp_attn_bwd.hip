@@ -5,226 +5,337 @@
 // probabilities of a step are recomputed exactly, P = exp(scale s - LSE), so each step adds
 // its own share:  dV += P^T dO,  dS = P o (dO V^T - delta),  dQ += scale dS K,  dK += scale dS^T Q.
 //
-// gfx950 design: two persistent kernels, because fp32 atomics retire at about one element
-// per L2 channel per clock on this chip (~270 G/s), far too few to accumulate dQ per key tile.
+// gfx950 design: two persistent kernels (dK/dV over key tiles in its own file, dQ here), because fp32 atomics
+// retire at about one element per L2 channel per clock on this chip (~270 G/s), far too few to accumulate dQ
+// per key tile.
 //
-//   dkv_kernel  unit = 128 keys of one segment of one work item x one KV head.  Wave w owns keys
-//               32w..32w+31: their K and V fragments and the fp32 accumulators dK^T, dV^T
-//               [channel x key] stay in registers while the unit loops over the query heads of
-//               the KV head and over the 32-row query blocks that see the tile.  S = Q K^T and
-//               dP = dO V^T come out as [query x key] with the key on the lane, which is exactly
-//               the B-operand layout of dV^T += dO^T P and dK^T += Q^T dS; dO^T / Q^T are
-//               transpose reads of the row-major LDS tiles.
-//   dq_kernel   unit = 128 query rows of one work item x one query head (the forward's shape).
-//               Wave w owns 32 rows, keeps Q and dO fragments in registers, streams K/V tiles
-//               through LDS, forms S^T = K Q^T and dP^T = V dO^T [key x query] so that dS^T is
-//               the B operand of dQ^T += K^T dS^T with K^T from transpose reads.
-//
-// Both add their result to the caller's fp32 accumulators once per unit: with plain
-// load-add-store when the scheduler found that no other item of the launch touches the same
-// rows (always the case for degree-1 sequences), otherwise with fp32 atomics.
+// dq_kernel: persistent 768-thread blocks (12 wave64, one block per CU, three waves per SIMD) pull
+// (query tile, query head) units from per-XCD counters.  A unit = 128 query rows of one work item for one query
+// head, looping over the 32-key blocks ("steps") of the two key segments that its rows see.  K and V blocks
+// stream through LDS in five stages filled by LDS-direct buffer loads; the K tile is chunk-permuted so that both
+// row reads and transpose reads run at the full LDS rate.  The three waves of a SIMD split a step by role (the
+// reasons are those given for the dK/dV kernel):
+//   P wave:  S^T = K Q^T [key x query] for its 32 query rows (Q fragments in registers, one query per lane, so
+//            LSE and the causal bound are per-lane constants), P^T = exp2(c S^T - LSE log2 e) with the mask,
+//            left in LDS in bf16 B-operand form;
+//   dS wave: dP^T - delta = V dO^T with the accumulator started at -delta (dO fragments in registers); one step
+//            later dS^T = P^T o (dP^T - delta) -> LDS bf16;
+//   dQ wave: dQ^T += K^T dS^T, two steps behind, for 64 channels x 64 query rows (the rows of two P waves), K^T
+//            by transpose reads, each feeding two matrix instructions.
+// One block barrier per step.  The result is added to the caller's fp32 accumulator once per unit: with plain
+// load-add-store when the scheduler found that no other item of the launch touches the same rows (always the
+// case for degree-1 sequences), otherwise with fp32 atomics.
 #include "fcp_bwd.h"
 
 namespace fcp {
 namespace {
 
-// ============================================================================================
-// dQ
-// ============================================================================================
 template <int D>
 struct DqCfg {
-  static constexpr int BM = kDqBM;                // 128 query rows per unit (32 per wave)
-  static constexpr int BN = kDqBN;                // 64 keys per LDS tile
-  static constexpr int KSTRIDE = D * 2 + 32;      // K rows: b128 row reads AND transpose reads
-  static constexpr int VSTRIDE = D * 2 + 16;      // V rows: b128 row reads only
-  static constexpr int KBYTES = BN * KSTRIDE;
-  static constexpr int VBYTES = BN * VSTRIDE;
-  static constexpr int STAGE = KBYTES + VBYTES;
-  static constexpr int LDS_BYTES = 2 * STAGE;
-  static constexpr int CHUNKS = BN * D * 2 / 16;
-  static constexpr int CPT = CHUNKS / 256;
-  static constexpr int CPR = D * 2 / 16;
+  static constexpr int BM = kDqBM;                 // 128 query rows per unit (32 per P / dS wave)
+  static constexpr int BK = 32;                    // keys per step
+  static constexpr int NWAVE = 12;
+  using DT = DualTile<D>;
+  static constexpr int TILE = DT::bytes(BK);       // one K or V block
+  static constexpr int STAGE = 2 * TILE;           // K, V
+  static constexpr int NSTAGE = 5;
+  static constexpr int PB = 32 * 32 * 2;           // P^T or dS^T of one query group in bf16, B-operand form
+  static constexpr int XGROUP = 2 * PB + 2 * PB;   // each double-buffered by step parity
+  static constexpr int XOFF = NSTAGE * STAGE;
+  static constexpr int LDS_BYTES = XOFF + 4 * XGROUP;
+  static constexpr int NS = D / 16;                // MFMAs of one 32 x 32 block of S^T or dP^T
+  static constexpr int NVA = D / 64;               // 32-channel blocks of dQ^T per dQ wave (half of the channels)
+  static constexpr int TINST = 2 * BK / DT::RPI;   // tile fill instructions per step (K then V)
+  static constexpr int kAhead = 4;
+  static_assert(TINST <= 2 * NWAVE, "at most two tile instructions per wave");
 };
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void dq_kernel(const BwdParams p) {
+__global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
   using C = DqCfg<D>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __shared__ int32_t s_unit;
+  using DT = typename C::DT;
+  extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
+  __shared__ int32_t s_next_unit;
+  __shared__ int32_t s_rec[16];
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int role = wave >> 2;                     // 0: P, 1: dS, 2: dQ
+  const int pw = wave & 3;                        // query group (and SIMD): rows 32 pw .. 32 pw + 31
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = p.hq / p.hkv;
+  const uint32_t lds0 = lds_offset(smem);
   const bool per_xcd = (p.hq % kNumXcd) == 0;
   const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
   const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
-  const int n_units = p.hdr->n_tiles * heads_here;
+  UnitQueue uq;
+  uq.init(p.hdr, p.tiles, xcd, heads_here, &s_next_unit, s_rec);
+
+  // ---- per-wave fill duty: tile instructions `wave` and `wave + 12` where they exist (the first half of the
+  // instructions fills K, the second V; instruction j covers block rows RPI (j % (TINST/2)) ..)
+  const int kv_row_bytes = p.hkv * D * 2;
+  int tfill[2], fill_dst[2];
+  bool fill_on[2], fill_is_v[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int j = wave + C::NWAVE * i;
+    fill_on[i] = j < C::TINST;
+    fill_is_v[i] = j >= C::TINST / 2;
+    const int row0 = DT::RPI * (j % (C::TINST / 2));
+    const int row = row0 + lane / DT::CPR;
+    tfill[i] = row * kv_row_bytes + (((lane % DT::CPR) ^ DT::key(row)) << 4);
+    fill_dst[i] = (fill_is_v[i] ? C::TILE : 0) + DT::row_base(row0);
+  }
+  const int n_fills = (fill_on[0] ? 1 : 0) + (fill_on[1] ? 1 : 0);
+
+  unsigned char* const xg = smem + C::XOFF + pw * C::XGROUP + lane * 16;
+  unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
+  unsigned char* const x_ds = xg + 2 * C::PB;
 
   for (;;) {
-    if (tid == 0) s_unit = atomicAdd(&p.hdr->counter[xcd], 1);
-    __syncthreads();
-    const int unit = __builtin_amdgcn_readfirstlane(s_unit);
-    __syncthreads();
-    if (unit >= n_units) break;
-    const int tile_i = unit / heads_here;
+    const int unit = uq.current(&s_next_unit);
+    if (unit >= uq.n_units) break;
+    const QTile t = read_record<QTile>(s_rec);
     const int head = xcd * heads_here + unit % heads_here;
     const int kvh = head / G;
-    const QTile t = *reinterpret_cast<const QTile*>(&p.tiles[tile_i]);
+    uq.prefetch();
+
     const bool exclusive = (t.flags & kFlagQExclusive) != 0;
-
     const int rows_here = t.rows;
-    const int wave_r0 = wave * 32;
-    const bool wave_active = wave_r0 < rows_here;
-    const int my_row = wave_r0 + l32;
-    const bool row_valid = my_row < rows_here;
-    const int row_ld = min(my_row, rows_here - 1);
-    const int q_pos = t.q_pos0 + my_row;
-    const int wave_first_pos = t.q_pos0 + wave_r0;
-    const int wave_last_pos = t.q_pos0 + min(wave_r0 + 31, rows_here - 1);
+    const int nt0 = (t.vis[0] + C::BK - 1) / C::BK, nt1 = (t.vis[1] + C::BK - 1) / C::BK;
+    const int n_iter = nt0 + nt1;
 
-    // Q and dO fragments: B operands (lane = query column), channels 16*ks + 8*g2 + [0,8)
-    bf16x8 qf[D / 16], dof[D / 16];
-    {
-      const int64_t off = ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
-        dof[ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
-      }
-    }
-    float lse2, delta;
-    {
-      const int64_t off = (int64_t)head * p.tq + t.q_row0 + row_ld;
-      const float l = p.lse[off];
-      lse2 = l == -INFINITY ? INFINITY : l * kLog2e;
-      delta = p.delta[off];
-    }
-
-    int vis[2], nt[2], k_seg_pos[2];
-    int64_t kv_row0[2];
-#pragma unroll
-    for (int s = 0; s < 2; ++s) {
-      vis[s] = t.vis[s];
-      nt[s] = (vis[s] + C::BN - 1) / C::BN;
-      kv_row0[s] = t.kv_row0[s];
-      k_seg_pos[s] = t.k_pos0[s];
-    }
-    const int n_iter = nt[0] + nt[1];
-
-    f32x16 dqacc[D / 32];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db) dqacc[db] = zero16();
-
-    u32x4 kreg[C::CPT], vreg[C::CPT];
-    auto issue_loads = [&](int it) {
-      const int s = it >= nt[0] ? 1 : 0;
-      const int kt = it - (s ? nt[0] : 0);
-      const int vl = vis[s];
-#pragma unroll
-      for (int c = 0; c < C::CPT; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        const int key = min(kt * C::BN + r, vl - 1);
-        const int64_t off = ((kv_row0[s] + key) * p.hkv + kvh) * D + col * 8;
-        kreg[c] = *reinterpret_cast<const u32x4*>(p.k + off);
-        vreg[c] = *reinterpret_cast<const u32x4*>(p.v + off);
-      }
+    // ---- fills ---------------------------------------------------------------------------------
+    // Step s = key block s of segment 0 for s < nt0, else block s - nt0 of segment 1.  The running state names
+    // the NEXT step to be filled; n_fills loads per call (past the last step they fall outside the empty
+    // resources' range), which the vmcnt waits rely on.  Keys past the segment's visible part lie outside the
+    // range and arrive as zeros.
+    int f_seg = nt0 > 0 ? 0 : 1, f_left = nt0 > 0 ? nt0 : nt1, f_soff = 0;
+    auto f_resource = [&](int i, int seg, bool live) {
+      const uint16_t* base = (fill_is_v[i] ? p.v : p.k) + ((int64_t)t.kv_row0[seg] * p.hkv + kvh) * D;
+      return buffer_rsrc(base, live ? (t.vis[seg] - 1) * kv_row_bytes + D * 2 : 0);
     };
-    auto store_tile = [&](int buf) {
-      unsigned char* kb = smem + buf * C::STAGE;
-      unsigned char* vb = kb + C::KBYTES;
-#pragma unroll
-      for (int c = 0; c < C::CPT; ++c) {
-        const int piece = tid + 256 * c;
-        const int r = piece / C::CPR, col = piece % C::CPR;
-        *reinterpret_cast<u32x4*>(kb + r * C::KSTRIDE + col * 16) = kreg[c];
-        *reinterpret_cast<u32x4*>(vb + r * C::VSTRIDE + col * 16) = vreg[c];
+    i32x4 f_r0 = f_resource(0, f_seg, n_iter > 0), f_r1 = f_resource(1, f_seg, n_iter > 0);
+    uint32_t f_dst = lds0;
+    auto fill_next = [&]() {
+      if (f_left == 0) {          // segment 1 (or past the end: empty resources)
+        const bool live = f_seg == 0 && nt1 > 0;
+        f_seg = 1;
+        f_left = live ? nt1 : (1 << 30);
+        f_soff = 0;
+        f_r0 = f_resource(0, 1, live);
+        f_r1 = f_resource(1, 1, live);
       }
+      if (fill_on[0]) lds_fill_b128(f_r0, f_dst + fill_dst[0], tfill[0], f_soff);
+      if (fill_on[1]) lds_fill_b128(f_r1, f_dst + fill_dst[1], tfill[1], f_soff);
+      --f_left;
+      f_soff += C::BK * kv_row_bytes;
+      f_dst += C::STAGE;
+      if (f_dst == lds0 + C::NSTAGE * C::STAGE) f_dst = lds0;
+    };
+    auto wait_fills = [&]() {     // all but the newest batch of this wave's fills have landed
+      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);
+      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 1);
+      else __builtin_amdgcn_s_waitcnt(0x0F70);
     };
 
-    if (n_iter > 0) {
-      issue_loads(0);
-      store_tile(0);
-    }
-    __syncthreads();
+    // Geometry of the steps, visited in order (one call per step): first key position and valid keys of the block.
+    int g_seg = nt0 > 0 ? 0 : 1, g_kt = 0;
+    int k_pos0, n_valid;
+    auto step_geometry = [&](int s) -> bool {
+      if (s >= n_iter) return false;
+      if (g_seg == 0 && g_kt == nt0) { g_seg = 1; g_kt = 0; }
+      k_pos0 = t.k_pos0[g_seg] + g_kt * C::BK;
+      n_valid = min(C::BK, t.vis[g_seg] - g_kt * C::BK);
+      ++g_kt;
+      return true;
+    };
+    // a query group has nothing to do in a step if it has no row in the tile or all its rows lie before the block
+    auto group_active = [&](int grp) { return 32 * grp < rows_here && k_pos0 <= t.q_pos0 + min(32 * grp + 31, rows_here - 1); };
+    const unsigned char* stage = smem;
+    auto next_stage = [&](const unsigned char* s) { s += C::STAGE; return s == smem + C::NSTAGE * C::STAGE ? smem : s; };
 
-    for (int it = 0; it < n_iter; ++it) {
-      const int buf = it & 1;
-      if (it + 1 < n_iter) issue_loads(it + 1);
-      const int s = it >= nt[0] ? 1 : 0;
-      const int kt = it - (s ? nt[0] : 0);
-      const int k_pos0 = k_seg_pos[s] + kt * C::BN;
-      const int n_valid = min(C::BN, vis[s] - kt * C::BN);
-      const bool wave_sees = wave_active && k_pos0 <= wave_last_pos;
-      const bool need_mask = (k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN);
-
-      if (wave_sees) {
-        const unsigned char* kb = smem + buf * C::STAGE;
-        const unsigned char* vb = kb + C::KBYTES;
-        // S^T = K Q^T and dP^T = V dO^T   [key x query], two 32-key blocks
-        f32x16 sacc[2], dpacc[2];
+    // Iteration `it` of the n_iter + 2 of a unit: the P and dS waves contract step it, the dS wave's vector phase
+    // works on step it - 1, the dQ wave on step it - 2.  At the top every wave has waited for all its fills but the
+    // newest batch (step it + 1) and met the others, so the blocks of steps it - 2 .. it are in LDS, P^T of step
+    // it - 1 and dS^T of step it - 2 are in their buffers, and the stage of step it - 3 is free for step it + 2.
+    if (role < 2) {
+      const int my_row = 32 * pw + l32;
+      const int row_ld = min(my_row, rows_here - 1);
+      // own-row fragments, B operand (lane = query column), channels 16 ks + 8 g2 + [0,8): Q (P wave) or dO (dS wave)
+      bf16x8 qf[C::NS];
+      {
+        const uint16_t* src = role == 0 ? p.q : p.d_o;
+        const int64_t off = ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk) {
-          sacc[kbk] = zero16();
-          dpacc[kbk] = zero16();
-          const unsigned char* krow = kb + (32 * kbk + l32) * C::KSTRIDE + 16 * g2;
-          const unsigned char* vrow = vb + (32 * kbk + l32) * C::VSTRIDE + 16 * g2;
+        for (int ks = 0; ks < C::NS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + off + 16 * ks);
+      }
+      // -LSE log2 e (P wave) or -delta (dS wave) of the lane's row
+      const float stat = p.stats[(int64_t)role * p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
+      // These loads must have arrived before the first fill is issued: the compiler, which does not see the fills,
+      // would otherwise wait for them inside the step loop with vmcnt(0), and that wait also covers every fill in
+      // flight.
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      fill_next();
+      fill_next();
+      int rowaddr[C::NS];          // row fragments (A operand): lane reads block row (key) l32, chunk 2 ks + g2
 #pragma unroll
-          for (int ks = 0; ks < D / 16; ++ks) {
-            const bf16x8 ak = *reinterpret_cast<const bf16x8*>(krow + 32 * ks);
-            sacc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qf[ks], sacc[kbk], 0, 0, 0);
-            const bf16x8 av = *reinterpret_cast<const bf16x8*>(vrow + 32 * ks);
-            dpacc[kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[ks], dpacc[kbk], 0, 0, 0);
-          }
+      for (int ks = 0; ks < C::NS; ++ks) rowaddr[ks] = tile_off<DT>(l32, 2 * ks + g2);
+      // S^T or dP^T - delta [32 keys x 32 own rows]; register i is key 8 (i/4) + 4 g2 + i%4 of the block
+      auto contract = [&](f32x16& sacc, const unsigned char* rtile) {
+        bf16x8 fr[C::NS];
+        auto request = [&](int x) { if (x < C::NS) fr[x] = *reinterpret_cast<const bf16x8*>(rtile + rowaddr[x]); };
+#pragma unroll
+        for (int x = 0; x < C::kAhead; ++x) request(x);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int x = 0; x < C::NS; ++x) {
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], qf[x], sacc, 0, 0, 0);
+          request(x + C::kAhead);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        // dS^T = P^T o (dP^T - delta); register i of block kbk is key 32*kbk + 8*(i/4) + 4*g2 + i%4
-        bf16x8 dsf[4];
+      };
+      if (role == 0) {
+        const int q_pos = t.q_pos0 + my_row;
+        const int first_pos = t.q_pos0 + 32 * pw;
+        for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
+          wait_fills();
+          __syncthreads();
+          fill_next();
+          if (!step_geometry(it) || !group_active(pw)) continue;
+          f32x16 sacc = zero16();
+          contract(sacc, stage);
+          // P^T = exp2(c S^T - LSE log2 e); masked where the key is past the block's valid keys or after the row.
+          // Rows past the tile's last row repeat the last row and are never stored.
+          const bool need_mask = (k_pos0 + C::BK - 1 > first_pos) || (n_valid < C::BK);
+          bf16x8 pb[2];
+          if (need_mask) {
+            int hi = min(n_valid, q_pos - k_pos0 + 1) - 4 * g2;     // keys (minus 4 g2) below this bound are seen
+            asm volatile("; masked variant" : "+v"(hi));
 #pragma unroll
-        for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            float pr = __builtin_amdgcn_exp2f(fmaf(sacc[kbk][i], p.scale_log2, -lse2));
-            if (need_mask) {
-              const int kk = 32 * kbk + 8 * (i / 4) + 4 * g2 + (i % 4);
-              if (kk >= n_valid || k_pos0 + kk > q_pos) pr = 0.f;
+            for (int i = 0; i < 16; ++i) {
+              const float e = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, stat));
+              pb[i / 8][i % 8] = (__bf16)((8 * (i / 4) + (i % 4) < hi) ? e : 0.f);
             }
-            dsf[2 * kbk + i / 8][i % 8] = (__bf16)(pr * (dpacc[kbk][i] - delta));
-          }
-        // dQ^T[channel, query] += K^T dS^T; A operand by transpose reads of the K tile
-        const unsigned char* kbase = kb + (4 * g2 + ((lane & 15) >> 2)) * C::KSTRIDE +
-                                     (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
-#pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db) {
-            const bf16x8 a = tr_read_8(kbase + (16 * t) * C::KSTRIDE + 64 * db, 8 * C::KSTRIDE);
-            dqacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dsf[t], dqacc[db], 0, 0, 0);
-          }
-      }
-      if (it + 1 < n_iter) store_tile(buf ^ 1);
-      __syncthreads();
-    }
-
-    // epilogue: dQ^T [channel x query] * scale -> accumulator rows
-    if (row_valid) {
-      float* dqp = p.dq + ((int64_t)(t.q_row0 + my_row) * p.hq + head) * D + 4 * g2;
-#pragma unroll
-      for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int c = 32 * db + 8 * r4;
-          if (exclusive) {
-            f32x4 a = *reinterpret_cast<f32x4*>(dqp + c);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) a[e] += dqacc[db][4 * r4 + e] * p.scale;
-            *reinterpret_cast<f32x4*>(dqp + c) = a;
           } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dqp + c + e, dqacc[db][4 * r4 + e] * p.scale);
+            for (int i = 0; i < 16; ++i) pb[i / 8][i % 8] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, stat));
           }
+#pragma unroll
+          for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_pb + (it & 1) * C::PB + j * 1024) = pb[j];
         }
+      } else {
+        bool prev_active = false;
+        f32x16 dpacc = zero16();   // dP^T - delta of step it - 1 at the top of iteration it
+        for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
+          wait_fills();
+          __syncthreads();
+          fill_next();
+          const bool active = step_geometry(it) && group_active(pw);
+          if (prev_active) {
+            // dS^T = P^T o (dP^T - delta) of step it - 1, with P as the matrix pipe would see it (bf16)
+            bf16x8 pin[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) pin[j] = *reinterpret_cast<const bf16x8*>(x_pb + ((it - 1) & 1) * C::PB + j * 1024);
+            bf16x8 dsb[2];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dsb[i / 8][i % 8] = (__bf16)((float)pin[i / 8][i % 8] * dpacc[i]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_ds + ((it - 1) & 1) * C::PB + j * 1024) = dsb[j];
+          }
+          if (active) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) dpacc[i] = stat;     // the accumulator starts at -delta of the lane's row
+            contract(dpacc, stage + C::TILE);
+          }
+          prev_active = active;
+        }
+      }
+    } else {
+      // dQ waves: 64 query rows (the groups 2 qp, 2 qp + 1 of two P / dS waves) x 64 channels (half ch).
+      const int qp = pw >> 1, ch = pw & 1;
+      // transposed fragments of the K block (A operand K^T [channel x key]; k-slots = keys 16 t + {4 g2 + [0,4),
+      // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
+      // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
+      int traddr[2][C::NVA];
+      {
+        const int row0 = 4 * g2 + ((lane & 15) >> 2);
+        const int chunk0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+          for (int db = 0; db < C::NVA; ++db)
+            traddr[h][db] = tile_off<DT>(row0 + 8 * h, 4 * (C::NVA * ch + db) + chunk0) + 8 * (lane & 1);
+      }
+      fill_next();
+      fill_next();
+      f32x16 acc[C::NVA][2];       // dQ^T [32-channel block][query group of the pair]: channel x query
+#pragma unroll
+      for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) acc[db][kb] = zero16();
+      constexpr int lag = 2;
+      const unsigned char* const xb = smem + C::XOFF + (2 * qp) * C::XGROUP + lane * 16 + 2 * C::PB;   // dS^T of group 2 qp + kb
+      const unsigned char* lstage = smem + (C::NSTAGE - lag) * C::STAGE;      // the stage of step it - lag
+      for (int it = 0; it < n_iter + 2; ++it, lstage = next_stage(lstage)) {
+        wait_fills();
+        __syncthreads();
+        fill_next();
+        const int s = it - lag;
+        if (s < 0 || !step_geometry(s)) continue;
+        const bool act0 = group_active(2 * qp), act1 = group_active(2 * qp + 1);
+        if (!act0 && !act1) continue;
+        // acc += K^T B: k-step tt of a B operand covers the block's keys 16 tt .. 16 tt + 15.  A group that was not
+        // active left nothing in its buffer: its operand is zero.
+        bf16x8 bop[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            bop[kb][tt] = *reinterpret_cast<const bf16x8*>(xb + kb * C::XGROUP + (s & 1) * C::PB + tt * 1024);
+            if (!(kb ? act1 : act0)) bop[kb][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+          }
+        constexpr int N = 2 * C::NVA;                              // fragments: (tt, db)
+        bf16x8 fr[N];
+#pragma unroll
+        for (int x = 0; x < N; ++x) {
+          const unsigned char* b0 = lstage + (x / C::NVA) * (16 * DT::row_base(1));
+          fr[x] = tr_read_8(b0 + traddr[0][x % C::NVA], b0 + traddr[1][x % C::NVA]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int x = 0; x < N; ++x)
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb) {
+            acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], bop[kb][x / C::NVA], acc[x % C::NVA][kb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+      }
+      // epilogue: dQ^T [channel x query] * scale -> accumulator rows
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const int row = 64 * qp + 32 * kb + l32;
+        if (row < rows_here) {
+          float* dst = p.dq + ((int64_t)(t.q_row0 + row) * p.hq + head) * D + 32 * C::NVA * ch + 4 * g2;
+#pragma unroll
+          for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+              const int c = 32 * db + 8 * r4;
+              if (exclusive) {
+                f32x4 a = *reinterpret_cast<f32x4*>(dst + c);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[e] += acc[db][kb][4 * r4 + e] * p.scale;
+                *reinterpret_cast<f32x4*>(dst + c) = a;
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + c + e, acc[db][kb][4 * r4 + e] * p.scale);
+              }
+            }
+        }
+      }
     }
+    uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }
 }
 
@@ -266,8 +377,8 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   const size_t need = fcp_scratch_bytes(FCP_SCRATCH_BWD, tq, tkv, hq, hkv, head_dim, n_work, 1);
   if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_bwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
 
-  if ((int64_t)tq * hq * head_dim * 2 >= ((int64_t)1 << 31))
-    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim * 2 must stay below 2^31 bytes");
+  if ((int64_t)tq * hq * head_dim * 2 >= ((int64_t)1 << 31) || (int64_t)tkv * hkv * head_dim * 2 >= ((int64_t)1 << 31))
+    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim * 2 and tkv * hkv * head_dim * 2 must stay below 2^31 bytes");
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap_kv = fcp::kv_tile_cap(tkv, n_work);
   const int64_t cap_q = fcp::q_tile_cap(tq, tkv, n_work, 1 << 20);
@@ -310,11 +421,11 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   if (head_dim == 128) {
     static bool done = false;
     if ((rc = fcp::set_lds_once(fcp::dq_kernel<128>, fcp::DqCfg<128>::LDS_BYTES, &done)) != FCP_OK) return rc;
-    hipLaunchKernelGGL(fcp::dq_kernel<128>, grid_for(cap_q * hq, 2), dim3(256), fcp::DqCfg<128>::LDS_BYTES, st, p);
+    hipLaunchKernelGGL(fcp::dq_kernel<128>, grid_for(cap_q * hq, 1), dim3(768), fcp::DqCfg<128>::LDS_BYTES, st, p);
   } else {
     static bool done = false;
     if ((rc = fcp::set_lds_once(fcp::dq_kernel<64>, fcp::DqCfg<64>::LDS_BYTES, &done)) != FCP_OK) return rc;
-    hipLaunchKernelGGL(fcp::dq_kernel<64>, grid_for(cap_q * hq, 2), dim3(256), fcp::DqCfg<64>::LDS_BYTES, st, p);
+    hipLaunchKernelGGL(fcp::dq_kernel<64>, grid_for(cap_q * hq, 1), dim3(768), fcp::DqCfg<64>::LDS_BYTES, st, p);
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;

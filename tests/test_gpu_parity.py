@@ -77,3 +77,46 @@ def test_many_short_sequences():
     q, k, v, do = synth.draw_qkvdo(wl)
     _say("40 short sequences, degree 1")
     check_rank(wl, q, k, v, do, 0, backward=True, label="shorts")
+
+
+def test_cfg2_full_size_sampled():
+    """The 32K-token packed workload in the launch configuration bench.py times (rank 0, 32 query / 8 KV heads,
+    D = 128).  The oracle cannot redo all of it in seconds, so: O, LSE and dQ of every 61st row of the rank for
+    the query heads of KV heads 0 and 5, and dK, dV of those two KV heads in full (their query heads, every row
+    of the rank) - heads are independent, so a head subset is the exact result for those heads."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    from oracle import plan as oplan
+    from parity import TOL_LSE_ABS, bf16_tensor_to_f64
+    wl = synth.make_workload(2)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    _say(f"cfg2 {wl.name} rank {wl.rank}: full-size run, sampled comparison")
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
+    ra.set_inputs(q, k, v, do)
+    ra.forward()
+    ra.backward()
+    torch.cuda.synchronize()
+    ochunks, _ = oplan.shard_plan(wl.seq_lens, wl.cp_degree)
+    rows = oplan.rank_rows(ochunks, wl.cu_seqlens, wl.rank)
+    assert len(rows) == ra.tq
+    O = bf16_tensor_to_f64(ra.o)
+    LSE = ra.lse.cpu().numpy().astype(np.float64).T
+    dQ, dK, dV = (bf16_tensor_to_f64(x) for x in (ra.dq, ra.dk, ra.dv))
+    for x in (O, LSE, dQ, dK, dV):
+        assert np.isfinite(x).all()
+    G = wl.hq // wl.hkv
+    sel = np.arange(0, len(rows), 61)
+    for kvh in (0, 5):
+        hs = slice(kvh * G, (kvh + 1) * G)
+        qs, dos = np.ascontiguousarray(q[:, hs]), np.ascontiguousarray(do[:, hs])
+        ks, vs = np.ascontiguousarray(k[:, kvh:kvh + 1]), np.ascontiguousarray(v[:, kvh:kvh + 1])
+        O_ref, LSE_ref = oattn.attn_fwd(qs, ks, vs, wl.cu_seqlens, wl.softmax_scale, rows)
+        assert rel_err(O[sel, hs], O_ref[sel]) <= TOL_BF16_REL
+        assert np.abs(LSE[sel, hs] - LSE_ref[sel]).max() <= TOL_LSE_ABS
+        dQ_ref = oattn.attn_dq(qs, ks, vs, dos, wl.cu_seqlens, wl.softmax_scale, rows[sel], O_ref[sel], LSE_ref[sel])
+        assert rel_err(dQ[sel, hs], dQ_ref) <= TOL_BF16_REL
+        dK_ref, dV_ref = oattn.attn_dkv(qs, ks, vs, dos, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref)
+        e = {"O": rel_err(O[sel, hs], O_ref[sel]), "dQ": rel_err(dQ[sel, hs], dQ_ref),
+             "dK": rel_err(dK[:, kvh:kvh + 1], dK_ref), "dV": rel_err(dV[:, kvh:kvh + 1], dV_ref)}
+        _say(f"  kv head {kvh}: {e}")
+        assert e["dK"] <= TOL_BF16_REL and e["dV"] <= TOL_BF16_REL
