@@ -25,6 +25,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per fcp_attn_bwd_step launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload only.
+MEASURED_BWD_TRAFFIC_BYTES = {"packed32k_lognormal24_h32x8_D128": 6.09e9}
 
 
 def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30):
@@ -58,6 +61,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="index into the five workloads (default: 32K packed)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy after the timed steps: the reference dispatch for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the ring steps of a CP group are simulated locally with all "
@@ -124,9 +130,9 @@ def main():
                    "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
                    "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
                    "seed": wl.seed},
-        "roofline": {"bound": "mfma", "kernel": "bwd_kernel<128> (fcp_attn_bwd_step)", "achieved": bwd_tflops,
-                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": bwd_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None},
+        "roofline": {"bound": "mfma", "kernel": f"fcp_attn_bwd_step (dkv_kernel<{wl.head_dim}> + dq_kernel<{wl.head_dim}>)",
+                     "achieved": bwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(wl.name)},
         "kernels": {
             "fwd_step": {"ms": seg_ms["fwd_step"], "tflops": fwd_tflops, "frac_mfma_peak": fwd_tflops / PEAK_BF16_TFLOPS},
             "bwd_step": {"ms": seg_ms["bwd_step"], "tflops": bwd_tflops, "frac_mfma_peak": bwd_tflops / PEAK_BF16_TFLOPS},
@@ -134,6 +140,13 @@ def main():
             "delta": {"ms": seg_ms["delta"]}, "zero": {"ms": seg_ms["zero"]}, "finalize": {"ms": seg_ms["finalize"]},
         },
     }
+    if args.copy_calibration:
+        src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, q, k, v, do, ra.rows)
     print(json.dumps(out))
