@@ -38,7 +38,8 @@ struct DqCfg {
   using DT = DualTile<D>;
   static constexpr int TILE = DT::bytes(BK);       // one K or V block
   static constexpr int STAGE = 2 * TILE;           // K, V
-  static constexpr int NSTAGE = 5;
+  static constexpr int FILL_AHEAD = 2;             // steps between a block's fill and its first use
+  static constexpr int NSTAGE = 3 + FILL_AHEAD;    // two steps behind, the step itself, FILL_AHEAD steps ahead
   static constexpr int PB = 32 * 32 * 2;           // P^T or dS^T of one query group in bf16, B-operand form
   static constexpr int XGROUP = 2 * PB + 2 * PB;   // each double-buffered by step parity
   static constexpr int XOFF = NSTAGE * STAGE;
@@ -102,7 +103,11 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 
     const bool exclusive = (t.flags & kFlagQExclusive) != 0;
     const int rows_here = t.rows;
-    const int nt0 = (t.vis[0] + C::BK - 1) / C::BK, nt1 = (t.vis[1] + C::BK - 1) / C::BK;
+    // the two segments' fields as scalars: indexing the record's arrays with a run-time segment number would put
+    // the record into scratch memory, and a scratch load inside the step loop waits with vmcnt(0), fills included
+    const int vis0 = t.vis[0], vis1 = t.vis[1], kpos0 = t.k_pos0[0], kpos1 = t.k_pos0[1];
+    const int64_t kvrow0 = t.kv_row0[0], kvrow1 = t.kv_row0[1];
+    const int nt0 = (vis0 + C::BK - 1) / C::BK, nt1 = (vis1 + C::BK - 1) / C::BK;
     const int n_iter = nt0 + nt1;
 
     // ---- fills ---------------------------------------------------------------------------------
@@ -112,8 +117,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     // range and arrive as zeros.
     int f_seg = nt0 > 0 ? 0 : 1, f_left = nt0 > 0 ? nt0 : nt1, f_soff = 0;
     auto f_resource = [&](int i, int seg, bool live) {
-      const uint16_t* base = (fill_is_v[i] ? p.v : p.k) + ((int64_t)t.kv_row0[seg] * p.hkv + kvh) * D;
-      return buffer_rsrc(base, live ? (t.vis[seg] - 1) * kv_row_bytes + D * 2 : 0);
+      const uint16_t* base = (fill_is_v[i] ? p.v : p.k) + ((seg ? kvrow1 : kvrow0) * p.hkv + kvh) * D;
+      return buffer_rsrc(base, live ? ((seg ? vis1 : vis0) - 1) * kv_row_bytes + D * 2 : 0);
     };
     i32x4 f_r0 = f_resource(0, f_seg, n_iter > 0), f_r1 = f_resource(1, f_seg, n_iter > 0);
     uint32_t f_dst = lds0;
@@ -134,8 +139,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       if (f_dst == lds0 + C::NSTAGE * C::STAGE) f_dst = lds0;
     };
     auto wait_fills = [&]() {     // all but the newest batch of this wave's fills have landed
-      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);
-      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 1);
+      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (C::FILL_AHEAD - 1)));
+      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
       else __builtin_amdgcn_s_waitcnt(0x0F70);
     };
 
@@ -145,8 +150,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     auto step_geometry = [&](int s) -> bool {
       if (s >= n_iter) return false;
       if (g_seg == 0 && g_kt == nt0) { g_seg = 1; g_kt = 0; }
-      k_pos0 = t.k_pos0[g_seg] + g_kt * C::BK;
-      n_valid = min(C::BK, t.vis[g_seg] - g_kt * C::BK);
+      k_pos0 = (g_seg ? kpos1 : kpos0) + g_kt * C::BK;
+      n_valid = min(C::BK, (g_seg ? vis1 : vis0) - g_kt * C::BK);
       ++g_kt;
       return true;
     };
@@ -162,6 +167,9 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     if (role < 2) {
       const int my_row = 32 * pw + l32;
       const int row_ld = min(my_row, rows_here - 1);
+      // The first fills go out before the wave's own loads so that their latencies overlap.
+#pragma unroll
+      for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
       // own-row fragments, B operand (lane = query column), channels 16 ks + 8 g2 + [0,8): Q (P wave) or dO (dS wave)
       bf16x8 qf[C::NS];
       {
@@ -172,12 +180,9 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       }
       // -LSE log2 e (P wave) or -delta (dS wave) of the lane's row
       const float stat = p.stats[(int64_t)role * p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
-      // These loads must have arrived before the first fill is issued: the compiler, which does not see the fills,
-      // would otherwise wait for them inside the step loop with vmcnt(0), and that wait also covers every fill in
-      // flight.
+      // These loads must have arrived before the step loop: the compiler, which does not see the fills, would
+      // otherwise wait for them inside the loop with vmcnt(0), and that wait also covers every fill in flight.
       __builtin_amdgcn_s_waitcnt(0x0F70);
-      fill_next();
-      fill_next();
       int rowaddr[C::NS];          // row fragments (A operand): lane reads block row (key) l32, chunk 2 ks + g2
 #pragma unroll
       for (int ks = 0; ks < C::NS; ++ks) rowaddr[ks] = tile_off<DT>(l32, 2 * ks + g2);
@@ -267,8 +272,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
           for (int db = 0; db < C::NVA; ++db)
             traddr[h][db] = tile_off<DT>(row0 + 8 * h, 4 * (C::NVA * ch + db) + chunk0) + 8 * (lane & 1);
       }
-      fill_next();
-      fill_next();
+#pragma unroll
+      for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
       f32x16 acc[C::NVA][2];       // dQ^T [32-channel block][query group of the pair]: channel x query
 #pragma unroll
       for (int db = 0; db < C::NVA; ++db)
@@ -293,8 +298,14 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt) {
             bop[kb][tt] = *reinterpret_cast<const bf16x8*>(xb + kb * C::XGROUP + (s & 1) * C::PB + tt * 1024);
-            if (!(kb ? act1 : act0)) bop[kb][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
           }
+        if (!(act0 && act1)) {     // rare (causal edge, tails): kept off the common path
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            if (!act0) bop[0][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (!act1) bop[1][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+          }
+        }
         constexpr int N = 2 * C::NVA;                              // fragments: (tt, db)
         bf16x8 fr[N];
 #pragma unroll

@@ -47,7 +47,8 @@ struct DkvCfg {
   static constexpr int TILE = DT::bytes(BM);       // one Q or dO block
   static constexpr int SLOT = 256;                 // one statistics plane of a step: 64 floats (32 used)
   static constexpr int STAGE = 2 * TILE + 2 * SLOT;   // Q, dO, -LSE log2 e, -delta
-  static constexpr int NSTAGE = 5;
+  static constexpr int FILL_AHEAD = 2;             // steps between a block's fill and its first use
+  static constexpr int NSTAGE = 3 + FILL_AHEAD;    // two steps behind, the step itself, FILL_AHEAD steps ahead
   // hand-over buffers of one key group, each double-buffered by step parity
   static constexpr int PB = 32 * 32 * 2;           // P or dS in bf16, B-operand form (2 x 16 bytes per lane)
   static constexpr int XGROUP = 2 * PB + 2 * PB;
@@ -158,8 +159,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     };
     // all but the newest batch of this wave's fills have landed
     auto wait_fills = [&]() {
-      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | 2);
-      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | 1);
+      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (C::FILL_AHEAD - 1)));
+      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
       else __builtin_amdgcn_s_waitcnt(0x0F70);
     };
 
@@ -185,6 +186,9 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     auto next_stage = [&](const unsigned char* s) { s += C::STAGE; return s == smem + C::NSTAGE * C::STAGE ? smem : s; };
 
     if (role == 0 || role == 2) {
+      // The first fills go out before the wave's own loads so that their latencies overlap.
+#pragma unroll
+      for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
       // own-key fragments, B operand (lane = key column): K for the P wave, V for the dS wave
       bf16x8 kvf[C::NS];
       {
@@ -192,13 +196,11 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         const int64_t off = ((kv_row0 + my_key_ld) * p.hkv + kvh) * D + 8 * g2;
 #pragma unroll
         for (int ks = 0; ks < C::NS; ++ks) kvf[ks] = *reinterpret_cast<const bf16x8*>(src + off + 16 * ks);
-        // The fragments must have arrived before the first fill is issued: the compiler, which does not see the
-        // fills, would otherwise wait for "its" loads inside the step loop with vmcnt(0), and that wait also covers
-        // every fill in flight.
+        // The fragments must have arrived before the step loop: the compiler, which does not see the fills, would
+        // otherwise wait for "its" loads inside the loop with vmcnt(0), and that wait also covers every fill in
+        // flight.
         __builtin_amdgcn_s_waitcnt(0x0F70);
       }
-      fill_next();
-      fill_next();
       // row fragments (A operands of S = Q K^T, dP = dO V^T): lane reads block row l32, chunk 2 ks + g2
       int rowaddr[C::NS];
 #pragma unroll
@@ -312,8 +314,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           for (int db = 0; db < C::NVA; ++db)
             traddr[h][db] = tile_off<DT>(row0 + 8 * h, 4 * (C::NVA * ch + db) + chunk0) + 8 * (lane & 1);
       }
-      fill_next();
-      fill_next();
+#pragma unroll
+      for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
       f32x16 acc[C::NVA][2];       // dV^T or dK^T [32-channel block][key group of the pair]: channel x key
 #pragma unroll
       for (int db = 0; db < C::NVA; ++db)
@@ -344,8 +346,14 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
 #pragma unroll
           for (int tt = 0; tt < 2; ++tt) {
             bop[kb][tt] = *reinterpret_cast<const bf16x8*>(xb + kb * C::XGROUP + (s & 1) * C::PB + tt * 1024);
-            if (!(kb ? act1 : act0)) bop[kb][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
           }
+        if (!(act0 && act1)) {     // rare (causal edge, tails): kept off the common path
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            if (!act0) bop[0][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (!act1) bop[1][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+          }
+        }
         const unsigned char* ttile = lstage + tsel;
         constexpr int N = 2 * C::NVA;                              // fragments: (tt, db)
         bf16x8 fr[N];

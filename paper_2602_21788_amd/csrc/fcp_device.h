@@ -70,9 +70,13 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 // Raw buffer resource: base address, no stride, `bytes` addressable bytes (accesses past them read as
 // zero), 32-bit untyped data format.
+// The four words are made wave-uniform explicitly (the first lane's values): the LDS-direct loads below take the
+// resource in scalar registers, and an operand the compiler cannot prove uniform would otherwise land in vector
+// registers, which the instruction does not accept.  `base` and `bytes` must be wave-uniform.
 __device__ inline i32x4 buffer_rsrc(const void* base, int bytes) {
   const uint64_t a = reinterpret_cast<uint64_t>(base);
-  const i32x4 r = {(int)(uint32_t)a, (int)((a >> 32) & 0xffffu), bytes, 0x00020000};
+  const i32x4 r = {__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu)),
+                   __builtin_amdgcn_readfirstlane(bytes), 0x00020000};
   return r;
 }
 
@@ -88,7 +92,7 @@ __device__ inline uint32_t lds_offset(const void* p) {
 // M0 is not used by anything else in these kernels.
 __device__ inline void lds_fill_b128(i32x4 rsrc, uint32_t lds, int voff, int soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-               :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+               :: "s"(__builtin_amdgcn_readfirstlane((int)lds)), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
 template <int D>
@@ -139,7 +143,7 @@ __device__ inline void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 3" ::: "m
 // One wave-wide LDS-direct load of one dword per lane: lane L's 4 bytes land at LDS offset lds + 4 L.
 __device__ inline void lds_fill_b32(i32x4 rsrc, uint32_t lds, int voff, int soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
-               :: "s"(lds), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+               :: "s"(__builtin_amdgcn_readfirstlane((int)lds)), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
 // Byte offset of chunk c of row `row` inside a tile.
