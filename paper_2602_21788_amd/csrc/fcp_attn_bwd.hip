@@ -87,7 +87,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     tfill[i] = row * kv_row_bytes + (((lane % DT::CPR) ^ DT::key(row)) << 4);
     fill_dst[i] = (fill_is_v[i] ? C::TILE : 0) + DT::row_base(row0);
   }
-  const int n_fills = (fill_on[0] ? 1 : 0) + (fill_on[1] ? 1 : 0);
 
   unsigned char* const xg = smem + C::XOFF + pw * C::XGROUP + lane * 16;
   unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
@@ -112,7 +111,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 
     // ---- fills ---------------------------------------------------------------------------------
     // Step s = key block s of segment 0 for s < nt0, else block s - nt0 of segment 1.  The running state names
-    // the NEXT step to be filled; n_fills loads per call (past the last step they fall outside the empty
+    // the NEXT step to be filled; the same loads in every call (past the last step they fall outside the empty
     // resources' range), which the vmcnt waits rely on.  Keys past the segment's visible part lie outside the
     // range and arrive as zeros.
     int f_seg = nt0 > 0 ? 0 : 1, f_left = nt0 > 0 ? nt0 : nt1, f_soff = 0;
@@ -139,9 +138,10 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       if (f_dst == lds0 + C::NSTAGE * C::STAGE) f_dst = lds0;
     };
     auto wait_fills = [&]() {     // all but the newest batch of this wave's fills have landed
-      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (C::FILL_AHEAD - 1)));
-      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
-      else __builtin_amdgcn_s_waitcnt(0x0F70);
+      // One wait for every wave (no branch on the wave's number of fills per step, 0..2): with at most
+      // FILL_AHEAD - 1 loads in flight everything older than the newest FILL_AHEAD - 1 batches has landed; a wave
+      // with two loads per step waits for a little more than it must.
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
     };
 
     // Geometry of the steps, visited in order (one call per step): first key position and valid keys of the block.

@@ -96,7 +96,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
   }
   const int stat_plane = (wave - C::TINST) & (C::NWAVE - 1);     // 0, 1: this wave loads that plane
   const bool fill_stat = stat_plane < 2;
-  const int n_fills = (fill_tile ? 1 : 0) + (fill_stat ? 1 : 0);  // loads per step of this wave
 
   unsigned char* const xg = smem + C::XOFF + pw * C::XGROUP + lane * 16;
   unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
@@ -126,7 +125,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
 
     // ---- fills ---------------------------------------------------------------------------------
     // Step s = (query head s / nqb of the KV head, query block qb0 + s % nqb).  The running state below names
-    // the NEXT step to be filled; steps are filled strictly in order, n_fills loads per call (past the last
+    // the NEXT step to be filled; steps are filled strictly in order, the same loads in every call (past the last
     // step they fall outside the empty resources' range), which the vmcnt waits rely on.  Rows past the item's
     // last row lie outside the range and arrive as zeros.
     const int q_bytes = (t.q_len - 1) * q_row_bytes + D * 2;
@@ -149,7 +148,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         f_ssoff = qb0 * C::BM * 4;
         f_resources(f_heads_left > 0, f_rt, f_rst);
       }
-      if (fill_tile) lds_fill_b128(f_rt, f_dst + (fill_is_do ? C::TILE : 0) + DT::row_base(fill_row0), tfill, f_soff);
+      if (C::TINST == C::NWAVE || fill_tile) lds_fill_b128(f_rt, f_dst + (fill_is_do ? C::TILE : 0) + DT::row_base(fill_row0), tfill, f_soff);
       if (fill_stat) lds_fill_b32(f_rst, f_dst + 2 * C::TILE + (stat_plane & 1) * C::SLOT, lane * 4, f_ssoff);
       --f_left;
       f_soff += C::BM * q_row_bytes;
@@ -159,9 +158,10 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     };
     // all but the newest batch of this wave's fills have landed
     auto wait_fills = [&]() {
-      if (n_fills == 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * (C::FILL_AHEAD - 1)));
-      else if (n_fills == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
-      else __builtin_amdgcn_s_waitcnt(0x0F70);
+      // One wait for every wave (no branch on the wave's number of fills per step, 0..2): with at most
+      // FILL_AHEAD - 1 loads in flight everything older than the newest FILL_AHEAD - 1 batches has landed; a wave
+      // with two loads per step waits for a little more than it must.
+      __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
     };
 
     // Iteration `it` of the n_iter + 2 of a unit: the P and dS waves work on step it, the dV wave and the dS
