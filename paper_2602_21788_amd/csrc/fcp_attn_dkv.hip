@@ -58,6 +58,7 @@ struct DkvCfg {
   static constexpr int NVA = D / 64;               // 32-channel blocks of dK^T / dV^T per accumulating wave (half of the channels)
   static constexpr int TINST = 2 * BM / DT::RPI;   // tile fill instructions per step (Q then dO), one per wave
   static constexpr int kAhead = 4;                 // LDS fragments requested this many MFMAs ahead
+  static constexpr int DRAIN = 3;                  // iterations after the last step's contraction (the dK wave's lag)
   static_assert(TINST <= NWAVE, "one tile instruction per wave");
   static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
@@ -164,8 +165,9 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
     };
 
-    // Iteration `it` of the n_iter + 2 of a unit: the P and dS waves work on step it, the dV wave and the dS
-    // wave's vector phase on step it - 1, the dK wave on step it - 2.  At the top every wave has waited for all
+    // Iteration `it` of the n_iter + DRAIN of a unit: the P and dS waves work on step it, the dS wave's vector phase
+    // on step it - 1, the dV wave on step it - 2, the dK wave on step it - 3 (both with operands requested in the
+    // iteration before).  At the top every wave has waited for all
     // its fills but the newest batch (step it + 1) and met the others, so the blocks of steps it - 2 .. it are
     // in LDS, P of step it - 1 and dS of step it - 2 are in their buffers, and the stage of step it - 3, last
     // read by the dK wave in iteration it - 1, is free for the fills of step it + 2.
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         }
       };
       if (role == 0) {
-        for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
+        for (int it = 0; it < n_iter + C::DRAIN; ++it, stage = next_stage(stage)) {
           pt.mark(0);
           wait_fills();
           __syncthreads();
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       } else {
         bool prev_active = false;
         f32x16 dpacc = zero16();   // dP - delta of step it - 1 at the top of iteration it
-        for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
+        for (int it = 0; it < n_iter + C::DRAIN; ++it, stage = next_stage(stage)) {
           pt.mark(0);
           wait_fills();
           __syncthreads();
@@ -321,56 +323,72 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) acc[db][kb] = zero16();
-      const int lag = role == 1 ? 1 : 2;
-      // B operands of the step, left by the pair's P / dS waves (same lane, key group 2 kp + kb)
+      // The dV wave runs two steps behind the P wave, the dK wave three: their operands are complete one barrier
+      // before they are used, so they are requested from LDS at the END of the iteration before (the LDS is then
+      // not serving the burst of requests that follows a barrier) and the matrix instructions start right after
+      // the barrier.
+      const int lag = role == 1 ? 2 : 3;
+      // B operands of a step, left by the pair's P / dS waves (same lane, key group 2 kp + kb)
       const unsigned char* const xb = smem + C::XOFF + (2 * kp) * C::XGROUP + lane * 16 + (role == 1 ? 0 : 2 * C::PB);
       const int tsel = role == 1 ? C::TILE : 0;                    // dO^T for dV, Q^T for dK
-      // the stage of step it - lag: start `lag` stages before stage 0
-      const unsigned char* lstage = smem + (C::NSTAGE - lag) * C::STAGE;
-      for (int it = 0; it < n_iter + 2; ++it, lstage = next_stage(lstage)) {
+      // the stage of step it + 1 - lag (the step whose operands iteration `it` requests)
+      const unsigned char* lstage = smem + (C::NSTAGE + 1 - lag) * C::STAGE;
+      constexpr int N = 2 * C::NVA;                                // fragments: (tt, db)
+      bf16x8 bop[2][2] = {}, fr[N] = {};                           // operands of the step of the next iteration
+      bool have = false, act0 = false, act1 = false;
+      for (int it = 0; it < n_iter + C::DRAIN; ++it, lstage = next_stage(lstage)) {
         pt.mark(0);
+        // the requests of the last iteration have been served: their sources may be overwritten after the barrier
+        __builtin_amdgcn_s_waitcnt(0xC07F);
         wait_fills();
         __syncthreads();
         pt.mark(1);
         fill_next();
-        const int s = it - lag;
-        int q_pos0;
-        if (s < 0 || !step_geometry(s, q_pos0)) continue;
-        const bool act0 = group_active(2 * kp), act1 = group_active(2 * kp + 1);
-        if (!act0 && !act1) continue;
-        // acc += T^T B: k-step tt of a B operand covers block rows 16 tt .. 16 tt + 15.  A group that was not active
-        // left nothing in its buffer: its operand is zero.
-        bf16x8 bop[2][2];
+        if (have) {
+          // acc += T^T B: k-step tt of a B operand covers block rows 16 tt .. 16 tt + 15.  A group that was not
+          // active left nothing in its buffer: its operand is zero.
+          if (!(act0 && act1)) {     // rare (causal edge, tails): kept off the common path
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            bop[kb][tt] = *reinterpret_cast<const bf16x8*>(xb + kb * C::XGROUP + (s & 1) * C::PB + tt * 1024);
+            for (int tt = 0; tt < 2; ++tt) {
+              if (!act0) bop[0][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+              if (!act1) bop[1][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
           }
-        if (!(act0 && act1)) {     // rare (causal edge, tails): kept off the common path
+          __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            if (!act0) bop[0][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            if (!act1) bop[1][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-          }
-        }
-        const unsigned char* ttile = lstage + tsel;
-        constexpr int N = 2 * C::NVA;                              // fragments: (tt, db)
-        bf16x8 fr[N];
+          for (int x = 0; x < N; ++x)
 #pragma unroll
-        for (int x = 0; x < N; ++x) {
-          const unsigned char* b0 = ttile + (x / C::NVA) * (16 * DT::row_base(1));
-          fr[x] = tr_read_8(b0 + traddr[0][x % C::NVA], b0 + traddr[1][x % C::NVA]);
+            for (int kb = 0; kb < 2; ++kb) {
+              acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], bop[kb][x / C::NVA], acc[x % C::NVA][kb], 0, 0, 0);
+              __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        __builtin_amdgcn_sched_barrier(0);
         pt.mark(2);
+        // requests for step s1 = it + 1 - lag: P of step s1 was written in iteration s1 <= it - 1 and dS of step s1 in
+        // iteration s1 + 1 <= it - 1, so both are visible since this iteration's barrier
+        const int s1 = it + 1 - lag;
+        int q_pos0;
+        have = false;
+        if (s1 >= 0 && step_geometry(s1, q_pos0)) {
+          act0 = group_active(2 * kp);
+          act1 = group_active(2 * kp + 1);
+          have = act0 || act1;
+        }
+        // (requested unconditionally: the addresses are valid LDS addresses for any s1, and registers that are
+        // written in every iteration need no copies around the loop)
+        {
 #pragma unroll
-        for (int x = 0; x < N; ++x)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
-            acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], bop[kb][x / C::NVA], acc[x % C::NVA][kb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int tt = 0; tt < 2; ++tt)
+              bop[kb][tt] = *reinterpret_cast<const bf16x8*>(xb + kb * C::XGROUP + (s1 & 1) * C::PB + tt * 1024);
+          const unsigned char* ttile = lstage + tsel;
+#pragma unroll
+          for (int x = 0; x < N; ++x) {
+            const unsigned char* b0 = ttile + (x / C::NVA) * (16 * DT::row_base(1));
+            fr[x] = tr_read_8(b0 + traddr[0][x % C::NVA], b0 + traddr[1][x % C::NVA]);
           }
+        }
         pt.mark(3);
       }
       // epilogue: dV^T or dK^T [channel x key] -> pool accumulators
