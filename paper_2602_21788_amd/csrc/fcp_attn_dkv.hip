@@ -171,23 +171,28 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     // its fills but the newest batch (step it + 1) and met the others, so the blocks of steps it - 2 .. it are
     // in LDS, P of step it - 1 and dS of step it - 2 are in their buffers, and the stage of step it - 3, last
     // read by the dK wave in iteration it - 1, is free for the fills of step it + 2.
-    // Geometry of step s for this wave's key group (steps are visited in order, one per call).
-    int qb = qb0;
-    int q_last;                  // position of the last row of the block (set by step_geometry)
-    auto step_geometry = [&](int s, int& q_pos0) -> bool {
-      const int row0 = qb * C::BM;
-      q_pos0 = t.q_seq_start + row0;
-      const int rows_here = min(C::BM, t.q_len - row0);
-      q_last = q_pos0 + rows_here - 1;
-      if (++qb == qb0 + nqb) qb = qb0;
-      return s < n_iter;
+    // Geometry.  Step s is block j = s % nqb of its head (the running counter `j` below, one advance per step).  A
+    // key group takes part in a block if it has keys in the tile and its first key is not after the block's last
+    // row, which holds from a first block on (first_active); its probabilities need the causal mask before a
+    // first block (first_unmasked) and always if the tile ends inside the group.  Both are found once per unit, so
+    // that a step costs one compare instead of the positions of its rows.
+    auto first_active = [&](int grp) {
+      const int thr = t.k_pos0 + 32 * grp - t.q_seq_start;      // first row of the sequence part that sees the group
+      if (32 * grp >= n_keys || thr > t.q_len - 1) return nqb;  // never
+      return max(0, (max(thr, 0) >> 5) - qb0);
     };
-    // a key group has nothing to contribute if it has no key in the tile or all its keys lie after the block's rows
-    auto group_active = [&](int grp) { return 32 * grp < n_keys && t.k_pos0 + 32 * grp <= q_last; };
+    auto first_unmasked = [&](int grp) {
+      if (32 * grp + 32 > n_keys) return nqb;                   // always masked
+      const int thr = t.k_pos0 + 32 * grp + 31 - t.q_seq_start; // first row that sees all of the group's keys
+      return max(0, ((max(thr, 0) + 31) >> 5) - qb0);
+    };
+    int j = 0;
+    auto next_block = [&]() { if (++j == nqb) j = 0; };
     const unsigned char* stage = smem;                        // stage of step `it`
     auto next_stage = [&](const unsigned char* s) { s += C::STAGE; return s == smem + C::NSTAGE * C::STAGE ? smem : s; };
 
     if (role == 0 || role == 2) {
+      const int j_act = first_active(pw), j_unmasked = first_unmasked(pw);
       // The first fills go out before the wave's own loads so that their latencies overlap.
 #pragma unroll
       for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
@@ -229,8 +234,9 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           __syncthreads();
           pt.mark(1);
           fill_next();
-          int q_pos0;
-          if (!step_geometry(it, q_pos0) || !group_active(pw)) continue;
+          const int jb = j;
+          next_block();
+          if (it >= n_iter || jb < j_act) continue;
           const float* stat = reinterpret_cast<const float*>(stage + 2 * C::TILE) + 4 * g2;
           f32x4 nl[4];           // -LSE log2 e of the rows of the lane's registers
 #pragma unroll
@@ -241,10 +247,11 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           // P = exp2(c S - LSE log2 e) with the mask.  Rows past the item's last row need no mask: their Q, dO
           // and statistics arrive as zeros, so P = 1 there meets dO = 0 in dV and dP - delta = 0 in dS.  That
           // leaves the causal edge and the keys past the tile's last.
-          const bool need_mask = (t.k_pos0 + 32 * pw + 31 > q_pos0) || (32 * pw + 32 > n_keys);
+          const bool need_mask = jb < j_unmasked;
           f32x4 pr[4];
           if (need_mask) {
             // register i is block row 8 (i/4) + 4 g2 + i%4; it sees the lane's key if that row >= key position - q_pos0
+            const int q_pos0 = t.q_seq_start + (qb0 + jb) * C::BM;
             int lo = (my_key_valid ? t.k_pos0 + my_key - q_pos0 : 1 << 20) - 4 * g2;
             asm volatile("; masked variant" : "+v"(lo));
 #pragma unroll
@@ -272,8 +279,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           __syncthreads();
           pt.mark(1);
           fill_next();
-          int q_pos0;
-          const bool active = step_geometry(it, q_pos0) && group_active(pw);
+          const bool active = it < n_iter && j >= j_act;
+          next_block();
           if (prev_active) {
             // dS = P o (dP - delta) of step it - 1, with P as the dV wave sees it (bf16)
             bf16x8 pin[2];
@@ -303,6 +310,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     } else {
       // Accumulating waves: 64 keys (the key groups 2 kp, 2 kp + 1 of two P / dS waves) x 64 channels (half ch).
       const int kp = pw >> 1, ch = pw & 1;
+      const int j_act0 = first_active(2 * kp), j_act1 = first_active(2 * kp + 1);
       // transposed fragments (A operands dO^T, Q^T [channel x query]; k-slots = query rows 16 t + {4 g2 + [0,4),
       // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
       // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
@@ -367,12 +375,14 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         // requests for step s1 = it + 1 - lag: P of step s1 was written in iteration s1 <= it - 1 and dS of step s1 in
         // iteration s1 + 1 <= it - 1, so both are visible since this iteration's barrier
         const int s1 = it + 1 - lag;
-        int q_pos0;
         have = false;
-        if (s1 >= 0 && step_geometry(s1, q_pos0)) {
-          act0 = group_active(2 * kp);
-          act1 = group_active(2 * kp + 1);
-          have = act0 || act1;
+        if (s1 >= 0) {
+          if (s1 < n_iter) {
+            act0 = j >= j_act0;
+            act1 = j >= j_act1;
+            have = act0 || act1;
+          }
+          next_block();
         }
         // (requested unconditionally: the addresses are valid LDS addresses for any s1, and registers that are
         // written in every iteration need no copies around the loop)
