@@ -144,19 +144,28 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
     };
 
-    // Geometry of the steps, visited in order (one call per step): first key position and valid keys of the block.
-    int g_seg = nt0 > 0 ? 0 : 1, g_kt = 0;
-    int k_pos0, n_valid;
-    auto step_geometry = [&](int s) -> bool {
-      if (s >= n_iter) return false;
-      if (g_seg == 0 && g_kt == nt0) { g_seg = 1; g_kt = 0; }
-      k_pos0 = (g_seg ? kpos1 : kpos0) + g_kt * C::BK;
-      n_valid = min(C::BK, (g_seg ? vis1 : vis0) - g_kt * C::BK);
-      ++g_kt;
-      return true;
+    // Geometry.  Step s < nt0 is key block s of segment 0, step s >= nt0 block s - nt0 of segment 1; inside a segment
+    // the key positions grow with the step.  A query group takes part in the leading blocks of a segment (those whose
+    // first key is not after the group's last row) and needs no mask in the leading blocks that all its rows see in
+    // full; both counts are found once per unit, so that a step costs a few compares instead of its positions.
+    struct Span { int a0, b1, u0, u1; };     // active: s < a0 or nt0 <= s < b1; unmasked: s < u0 or nt0 <= s < u1
+    auto group_span = [&](int grp) {
+      Span sp = {0, 0, 0, 0};
+      if (32 * grp >= rows_here) return sp;
+      const int first = t.q_pos0 + 32 * grp, last = t.q_pos0 + min(32 * grp + 31, rows_here - 1);
+      auto count = [&](int kpos, int vis, int nt, int& act, int& unm) {
+        act = last >= kpos ? min(nt, ((last - kpos) >> 5) + 1) : 0;                 // blocks with kpos + 32 kt <= last
+        const int full = first - kpos - 31 >= 0 ? ((first - kpos - 31) >> 5) + 1 : 0;   // ... with kpos + 32 kt + 31 <= first
+        unm = min(full, vis / C::BK);                                              // and all 32 keys valid
+      };
+      int a1, u1;
+      count(kpos0, vis0, nt0, sp.a0, sp.u0);
+      count(kpos1, vis1, nt1, a1, u1);
+      sp.b1 = nt0 + a1;
+      sp.u1 = nt0 + u1;
+      return sp;
     };
-    // a query group has nothing to do in a step if it has no row in the tile or all its rows lie before the block
-    auto group_active = [&](int grp) { return 32 * grp < rows_here && k_pos0 <= t.q_pos0 + min(32 * grp + 31, rows_here - 1); };
+    auto in_span = [&](int s, int lo_end, int hi_end) { return s < lo_end || (s >= nt0 && s < hi_end); };
     const unsigned char* stage = smem;
     auto next_stage = [&](const unsigned char* s) { s += C::STAGE; return s == smem + C::NSTAGE * C::STAGE ? smem : s; };
 
@@ -165,6 +174,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     // newest batch (step it + 1) and met the others, so the blocks of steps it - 2 .. it are in LDS, P^T of step
     // it - 1 and dS^T of step it - 2 are in their buffers, and the stage of step it - 3 is free for step it + 2.
     if (role < 2) {
+      const Span sp = group_span(pw);
       const int my_row = 32 * pw + l32;
       const int row_ld = min(my_row, rows_here - 1);
       // The first fills go out before the wave's own loads so that their latencies overlap.
@@ -202,19 +212,22 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       };
       if (role == 0) {
         const int q_pos = t.q_pos0 + my_row;
-        const int first_pos = t.q_pos0 + 32 * pw;
         for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
           wait_fills();
           __syncthreads();
           fill_next();
-          if (!step_geometry(it) || !group_active(pw)) continue;
+          if (!in_span(it, sp.a0, sp.b1)) continue;
           f32x16 sacc = zero16();
           contract(sacc, stage);
           // P^T = exp2(c S^T - LSE log2 e); masked where the key is past the block's valid keys or after the row.
           // Rows past the tile's last row repeat the last row and are never stored.
-          const bool need_mask = (k_pos0 + C::BK - 1 > first_pos) || (n_valid < C::BK);
+          const bool need_mask = !in_span(it, sp.u0, sp.u1);
           bf16x8 pb[2];
           if (need_mask) {
+            const bool seg1 = it >= nt0;
+            const int kt = it - (seg1 ? nt0 : 0);
+            const int k_pos0 = (seg1 ? kpos1 : kpos0) + kt * C::BK;
+            const int n_valid = min(C::BK, (seg1 ? vis1 : vis0) - kt * C::BK);
             int hi = min(n_valid, q_pos - k_pos0 + 1) - 4 * g2;     // keys (minus 4 g2) below this bound are seen
             asm volatile("; masked variant" : "+v"(hi));
 #pragma unroll
@@ -236,7 +249,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
           wait_fills();
           __syncthreads();
           fill_next();
-          const bool active = step_geometry(it) && group_active(pw);
+          const bool active = in_span(it, sp.a0, sp.b1);
           if (prev_active) {
             // dS^T = P^T o (dP^T - delta) of step it - 1, with P as the matrix pipe would see it (bf16)
             bf16x8 pin[2];
@@ -259,6 +272,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     } else {
       // dQ waves: 64 query rows (the groups 2 qp, 2 qp + 1 of two P / dS waves) x 64 channels (half ch).
       const int qp = pw >> 1, ch = pw & 1;
+      const Span sp0 = group_span(2 * qp), sp1 = group_span(2 * qp + 1);
       // transposed fragments of the K block (A operand K^T [channel x key]; k-slots = keys 16 t + {4 g2 + [0,4),
       // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
       // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
@@ -287,8 +301,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         __syncthreads();
         fill_next();
         const int s = it - lag;
-        if (s < 0 || !step_geometry(s)) continue;
-        const bool act0 = group_active(2 * qp), act1 = group_active(2 * qp + 1);
+        if (s < 0) continue;
+        const bool act0 = in_span(s, sp0.a0, sp0.b1), act1 = in_span(s, sp1.a0, sp1.b1);
         if (!act0 && !act1) continue;
         // acc += K^T B: k-step tt of a B operand covers the block's keys 16 tt .. 16 tt + 15.  A group that was not
         // active left nothing in its buffer: its operand is zero.
