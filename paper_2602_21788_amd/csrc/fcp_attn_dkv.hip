@@ -408,21 +408,29 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         const int key = 64 * kp + 32 * kb + l32;
         if (key < n_keys) {
           float* dst = (role == 1 ? p.dv : p.dk) + ((kv_row0 + key) * p.hkv + kvh) * D + 32 * C::NVA * ch + 4 * g2;
+          if (exclusive) {
+            // all loads of the row first, one wait, then the adds and stores (not one round trip per 16 bytes)
+            f32x4 a[C::NVA][4];
 #pragma unroll
-          for (int db = 0; db < C::NVA; ++db)
+            for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-              const int c = 32 * db + 8 * r4;
-              if (exclusive) {
-                f32x4 a = *reinterpret_cast<f32x4*>(dst + c);
+              for (int r4 = 0; r4 < 4; ++r4) a[db][r4] = *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * r4);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) a[e] += acc[db][kb][4 * r4 + e] * mul;
-                *reinterpret_cast<f32x4*>(dst + c) = a;
-              } else {
+            for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + c + e, acc[db][kb][4 * r4 + e] * mul);
+              for (int r4 = 0; r4 < 4; ++r4) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[db][r4][e] += acc[db][kb][4 * r4 + e] * mul;
+                *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * r4) = a[db][r4];
               }
-            }
+          } else {
+#pragma unroll
+            for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+              for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + 32 * db + 8 * r4 + e, acc[db][kb][4 * r4 + e] * mul);
+          }
         }
       }
     }
