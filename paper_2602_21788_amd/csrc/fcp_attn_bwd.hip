@@ -92,7 +92,10 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
   unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
   unsigned char* const x_ds = xg + 2 * C::PB;
 
+  PhaseTimer pt;
+  pt.begin();
   for (;;) {
+    pt.mark(0);
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
     const QTile t = read_record<QTile>(s_rec);
@@ -212,6 +215,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       };
       if (role == 0) {
         const int q_pos = t.q_pos0 + my_row;
+        pt.mark(1);
         for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
           wait_fills();
           __syncthreads();
@@ -242,6 +246,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 #pragma unroll
           for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_pb + (it & 1) * C::PB + j * 1024) = pb[j];
         }
+        pt.mark(2);
       } else {
         bool prev_active = false;
         f32x16 dpacc = zero16();   // dP^T - delta of step it - 1 at the top of iteration it
@@ -296,6 +301,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       constexpr int lag = 2;
       const unsigned char* const xb = smem + C::XOFF + (2 * qp) * C::XGROUP + lane * 16 + 2 * C::PB;   // dS^T of group 2 qp + kb
       const unsigned char* lstage = smem + (C::NSTAGE - lag) * C::STAGE;      // the stage of step it - lag
+      pt.mark(1);
       for (int it = 0; it < n_iter + 2; ++it, lstage = next_stage(lstage)) {
         wait_fills();
         __syncthreads();
@@ -336,6 +342,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
             __builtin_amdgcn_sched_barrier(0);
           }
       }
+      pt.mark(2);
       // epilogue: dQ^T [channel x query] * scale -> accumulator rows
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
@@ -368,8 +375,11 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         }
       }
     }
+    pt.mark(3);
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
+    pt.mark(4);
   }
+  pt.end(p.hdr);
 }
 
 template <typename K>

@@ -239,7 +239,10 @@ struct UnitQueue {
       if (lane < 16) s_rec[lane] = recw;
       if (lane == 0) *s_next = idx1;
     }
-    __syncthreads();
+    // LDS-only barrier: the unit's last stores and atomics to global memory stay in flight (a __syncthreads() would
+    // wait for them here, several microseconds per unit); nothing in the block reads them back.
+    __builtin_amdgcn_s_waitcnt(0xC07F);      // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
   }
 };
 
