@@ -74,13 +74,6 @@ struct FwdCfg {
   static_assert(RPW % KT::RPI == 0 && FILLS < 16, "fill split");
 };
 
-#ifdef FCP_TIMING
-// development aid: one wave of every block adds the cycles between the marks of a step to the spare words of
-// the schedule header (0: matrix slot, 1: boundary, 2: vector slot, 3: boundary; units of 16 cycles)
-#define FCP_T(i) do { if (tid == FCP_TIMING * 64) { const long long now_ = __builtin_readcyclecounter(); if ((i) > 0) tacc[(i) - 1] += now_ - tlast; tlast = now_; } } while (0)
-#else
-#define FCP_T(i) do {} while (0)
-#endif
 
 template <int D>
 __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
@@ -129,10 +122,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     for (int db = 0; db < C::NVA; ++db) vaddr[db] = C::KBYTES + tile_off<VT>(row0, 4 * db + chunk0) + 8 * (lane & 1);
   }
 
-#ifdef FCP_TIMING
-  long long tacc[4] = {0, 0, 0, 0}, tlast = 0;
-  const long long tstart = __builtin_readcyclecounter();
-#endif
+  PhaseTimer pt;
+  pt.begin();
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
@@ -326,9 +317,9 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     using T = std::true_type;
     using F = std::false_type;
     for (int it = 0; it <= n_iter; ++it) {
-      FCP_T(0);
+      pt.mark(0);
       fill_next();
-      FCP_T(1);
+      pt.mark(1);
       const bool do_s = it < n_w, do_pv = it > 0 && it - 1 < n_w;
       // the matrix stream goes first at the SIMD's issue port: an MFMA is wanted every 32 cycles and must not
       // queue behind the partner wave's vector instructions
@@ -337,12 +328,12 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       else if (do_s) matrix_slot(T{}, F{}, it);
       else if (do_pv) matrix_slot(F{}, T{}, it);
       __builtin_amdgcn_s_setprio(0);
-      FCP_T(2);
+      pt.mark(2);
       boundary();
       if (do_s) vector_slot(it);
-      FCP_T(3);
+      pt.mark(3);
       boundary();
-      FCP_T(4);
+      pt.mark(4);
     }
     if (grp == 0) __syncthreads();
 
@@ -367,12 +358,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     }
     uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block (barrier: LDS stages are free)
   }
-#ifdef FCP_TIMING
-  if (tid == FCP_TIMING * 64) {
-    for (int i = 0; i < 4; ++i) atomicAdd(&p.hdr->pad1[i], (int32_t)(tacc[i] >> 4));
-    atomicAdd(&p.hdr->pad0, (int32_t)((__builtin_readcyclecounter() - tstart) >> 8));
-  }
-#endif
+  pt.end(p.hdr);
 }
 
 }  // namespace

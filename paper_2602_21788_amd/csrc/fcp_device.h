@@ -130,16 +130,6 @@ struct DualTile {
   __host__ __device__ static constexpr int bytes(int rows) { return rows * D * 2; }
 };
 
-// acc += A B (v_mfma_f32_32x32x16_bf16) with the accumulator held in ACCUMULATION registers (AGPRs): long-lived
-// accumulators stay out of the vector register file.  The compiler does not know that this is a matrix
-// instruction, so two hazards are the caller's: at least two other MFMAs (or mfma_settle) between two MFMAs
-// on the same accumulator, and mfma_settle() before anything else reads or writes an accumulator just written.
-__device__ inline void mfma_acc(f32x16& acc, bf16x8 a, bf16x8 b) {
-  asm("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
-}
-// 20 wait states: more than the 8 passes + 2 of the matrix instruction above.
-__device__ inline void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 3" ::: "memory"); }
-
 // One wave-wide LDS-direct load of one dword per lane: lane L's 4 bytes land at LDS offset lds + 4 L.
 __device__ inline void lds_fill_b32(i32x4 rsrc, uint32_t lds, int voff, int soff) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
@@ -158,11 +148,6 @@ __device__ inline int fill_voff(int rpw, int wave, int i, int lane, int row_byte
   const int row = rpw * wave + T::RPI * i + lane / T::CPR;
   return row * row_bytes + (((lane % T::CPR) ^ T::key(row)) << 4);
 }
-
-// Scheduling groups (llvm.amdgcn.sched.group.barrier): the next `n` instructions of class `mask` in
-// the issue order of the enclosing basic block.
-constexpr int kSgValu = 0x002, kSgMfma = 0x008, kSgDsRead = 0x100, kSgDsWrite = 0x200, kSgVmemRead = 0x020;
-#define sched_group(mask, n) __builtin_amdgcn_sched_group_barrier((mask), (n), 0)
 
 // Development aid (compiled in with -DFCP_TIMING=<wave>): that wave of every block accumulates the shader
 // cycles between consecutive marks i-1 -> i (i = 1..4) and adds them, in units of 16 cycles, to the four spare
