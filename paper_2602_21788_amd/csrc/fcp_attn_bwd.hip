@@ -278,7 +278,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       // dQ waves: 64 query rows (the groups 2 qp, 2 qp + 1 of two P / dS waves) x 64 channels (half ch).
       const int qp = pw >> 1, ch = pw & 1;
       const Span sp0 = group_span(2 * qp), sp1 = group_span(2 * qp + 1);
-      // transposed fragments of the K block (A operand K^T [channel x key]; k-slots = keys 16 t + {4 g2 + [0,4),
+      // transposed fragments of the K block (B operand K [key x channel], one channel per lane; k-slots = keys 16 t + {4 g2 + [0,4),
       // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
       // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
       int traddr[2][C::NVA];
@@ -293,11 +293,44 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       }
 #pragma unroll
       for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
-      f32x16 acc[C::NVA][2];       // dQ^T [32-channel block][query group of the pair]: channel x query
+      // dQ [32-channel block][query group of the pair] as [query x channel]: the channel is on the lane, register i is
+      // row 8 (i/4) + 4 g2 + i%4 of the group, so that a wave-wide access covers whole 128-byte lines of two rows.
+      // When no other item of the launch touches the tile's rows the accumulators START at the caller's values
+      // (divided by the scale that the epilogue applies) and the epilogue only stores: the loads overlap the other
+      // waves' prologue loads instead of standing, as a read-modify-write at the end, between two units.
+      // The rows are reached through a buffer resource that ends with the tile's last row (reads past it give zero,
+      // writes are dropped): per-lane offset = the lane's part (row 4 g2 of a group of eight, channel l32), scalar
+      // offset = the rest.
+      f32x16 acc[C::NVA][2];
+      const int row_bytes = p.hq * D * 4;
+      const int n_pair_rows = rows_here - 64 * qp;                 // rows of the tile in this wave's 64-row half
+      const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(p.dq + ((int64_t)(t.q_row0 + 64 * qp) * p.hq + head) * D + 32 * C::NVA * ch), (short)0,
+          n_pair_rows > 0 ? (n_pair_rows - 1) * row_bytes + 32 * C::NVA * 4 : 0, 0x00020000);
+      const int acc_voff = 4 * g2 * row_bytes + 4 * l32;
+      auto acc_soff = [&](int kb, int db, int i) { return (32 * kb + 8 * (i / 4) + (i % 4)) * row_bytes + 128 * db; };
 #pragma unroll
-      for (int db = 0; db < C::NVA; ++db)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) acc[db][kb] = zero16();
+        for (int db = 0; db < C::NVA; ++db) {
+          acc[db][kb] = zero16();
+          if (exclusive) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              acc[db][kb][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(racc, acc_voff, acc_soff(kb, db, i), 0));
+          }
+        }
+      // (explicit wait: see the note at the P / dS waves' loads)
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      if (exclusive) {
+        const float inv_scale = 1.f / p.scale;
+#pragma unroll
+        for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[db][kb][i] *= inv_scale;
+      }
       constexpr int lag = 2;
       const unsigned char* const xb = smem + C::XOFF + (2 * qp) * C::XGROUP + lane * 16 + 2 * C::PB;   // dS^T of group 2 qp + kb
       const unsigned char* lstage = smem + (C::NSTAGE - lag) * C::STAGE;      // the stage of step it - lag
@@ -310,7 +343,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         if (s < 0) continue;
         const bool act0 = in_span(s, sp0.a0, sp0.b1), act1 = in_span(s, sp1.a0, sp1.b1);
         if (!act0 && !act1) continue;
-        // acc += K^T B: k-step tt of a B operand covers the block's keys 16 tt .. 16 tt + 15.  A group that was not
+        // acc += dS K: k-step tt of a dS operand covers the block's keys 16 tt .. 16 tt + 15.  A group that was not
         // active left nothing in its buffer: its operand is zero.
         bf16x8 bop[2][2];
 #pragma unroll
@@ -338,42 +371,22 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         for (int x = 0; x < N; ++x)
 #pragma unroll
           for (int kb = 0; kb < 2; ++kb) {
-            acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], bop[kb][x / C::NVA], acc[x % C::NVA][kb], 0, 0, 0);
+            acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[kb][x / C::NVA], fr[x], acc[x % C::NVA][kb], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
           }
       }
       pt.mark(2);
-      // epilogue: dQ^T [channel x query] * scale -> accumulator rows
+      // epilogue: dQ [query x channel] * scale -> accumulator rows
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const int row = 64 * qp + 32 * kb + l32;
-        if (row < rows_here) {
-          float* dst = p.dq + ((int64_t)(t.q_row0 + row) * p.hq + head) * D + 32 * C::NVA * ch + 4 * g2;
-          if (exclusive) {
-            // all loads of the row first, one wait, then the adds and stores (not one round trip per 16 bytes)
-            f32x4 a[C::NVA][4];
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int db = 0; db < C::NVA; ++db)
+        for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4) a[db][r4] = *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * r4);
-#pragma unroll
-            for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) a[db][r4][e] += acc[db][kb][4 * r4 + e] * p.scale;
-                *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * r4) = a[db][r4];
-              }
-          } else {
-#pragma unroll
-            for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + 32 * db + 8 * r4 + e, acc[db][kb][4 * r4 + e] * p.scale);
+          for (int i = 0; i < 16; ++i) {
+            const float val = acc[db][kb][i] * p.scale;
+            if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
+            else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
           }
-        }
-      }
     }
     pt.mark(3);
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
