@@ -311,7 +311,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       // Accumulating waves: 64 keys (the key groups 2 kp, 2 kp + 1 of two P / dS waves) x 64 channels (half ch).
       const int kp = pw >> 1, ch = pw & 1;
       const int j_act0 = first_active(2 * kp), j_act1 = first_active(2 * kp + 1);
-      // transposed fragments (A operands dO^T, Q^T [channel x query]; k-slots = query rows 16 t + {4 g2 + [0,4),
+      // transposed fragments (B operands dO, Q [query x channel], one channel per lane; k-slots = query rows 16 t + {4 g2 + [0,4),
       // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
       // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
       int traddr[2][C::NVA];
@@ -326,11 +326,44 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       }
 #pragma unroll
       for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
-      f32x16 acc[C::NVA][2];       // dV^T or dK^T [32-channel block][key group of the pair]: channel x key
+      // dV or dK [32-channel block][key group of the pair] as [key x channel]: the channel is on the lane, register i
+      // is key 8 (i/4) + 4 g2 + i%4 of the group, so that a wave-wide access covers whole 128-byte lines of two keys.
+      // When no other item of the launch touches the tile's keys the accumulators START at the caller's values
+      // (divided by the factor that the epilogue applies) and the epilogue only stores.  The keys are reached
+      // through a buffer resource that ends with the tile's last key (reads past it give zero, writes are
+      // dropped): per-lane offset = the lane's part (key 4 g2 of a group of eight, channel l32), scalar offset = the
+      // rest.
+      f32x16 acc[C::NVA][2];
+      const float mul = role == 1 ? 1.f : p.scale;
+      const int row_bytes = p.hkv * D * 4;
+      const int n_pair_keys = n_keys - 64 * kp;                    // keys of the tile in this wave's 64-key half
+      const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)((role == 1 ? p.dv : p.dk) + ((kv_row0 + 64 * kp) * p.hkv + kvh) * D + 32 * C::NVA * ch), (short)0,
+          n_pair_keys > 0 ? (n_pair_keys - 1) * row_bytes + 32 * C::NVA * 4 : 0, 0x00020000);
+      const int acc_voff = 4 * g2 * row_bytes + 4 * l32;
+      auto acc_soff = [&](int kb, int db, int i) { return (32 * kb + 8 * (i / 4) + (i % 4)) * row_bytes + 128 * db; };
 #pragma unroll
-      for (int db = 0; db < C::NVA; ++db)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) acc[db][kb] = zero16();
+        for (int db = 0; db < C::NVA; ++db) {
+          acc[db][kb] = zero16();
+          if (exclusive) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              acc[db][kb][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(racc, acc_voff, acc_soff(kb, db, i), 0));
+          }
+        }
+      // (explicit wait: the compiler must not be left to wait for these loads inside the step loop)
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      if (exclusive && role != 1) {
+        const float inv = 1.f / p.scale;
+#pragma unroll
+        for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[db][kb][i] *= inv;
+      }
       // The dV wave runs two steps behind the P wave, the dK wave three: their operands are complete one barrier
       // before they are used, so they are requested from LDS at the END of the iteration before (the LDS is then
       // not serving the burst of requests that follows a barrier) and the matrix instructions start right after
@@ -353,8 +386,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         pt.mark(1);
         fill_next();
         if (have) {
-          // acc += T^T B: k-step tt of a B operand covers block rows 16 tt .. 16 tt + 15.  A group that was not
-          // active left nothing in its buffer: its operand is zero.
+          // acc += P^T dO (dS^T Q): k-step tt of a P (dS) operand covers block rows 16 tt .. 16 tt + 15.  A group that
+          // was not active left nothing in its buffer: its operand is zero.
           if (!(act0 && act1)) {     // rare (causal edge, tails): kept off the common path
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
@@ -367,7 +400,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           for (int x = 0; x < N; ++x)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-              acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], bop[kb][x / C::NVA], acc[x % C::NVA][kb], 0, 0, 0);
+              acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[kb][x / C::NVA], fr[x], acc[x % C::NVA][kb], 0, 0, 0);
               __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -401,38 +434,17 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         }
         pt.mark(3);
       }
-      // epilogue: dV^T or dK^T [channel x key] -> pool accumulators
-      const float mul = role == 1 ? 1.f : p.scale;
+      // epilogue: dV or dK [key x channel] -> pool accumulators
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const int key = 64 * kp + 32 * kb + l32;
-        if (key < n_keys) {
-          float* dst = (role == 1 ? p.dv : p.dk) + ((kv_row0 + key) * p.hkv + kvh) * D + 32 * C::NVA * ch + 4 * g2;
-          if (exclusive) {
-            // all loads of the row first, one wait, then the adds and stores (not one round trip per 16 bytes)
-            f32x4 a[C::NVA][4];
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int db = 0; db < C::NVA; ++db)
+        for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4) a[db][r4] = *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * r4);
-#pragma unroll
-            for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) a[db][r4][e] += acc[db][kb][4 * r4 + e] * mul;
-                *reinterpret_cast<f32x4*>(dst + 32 * db + 8 * r4) = a[db][r4];
-              }
-          } else {
-#pragma unroll
-            for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-              for (int r4 = 0; r4 < 4; ++r4)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) unsafeAtomicAdd(dst + 32 * db + 8 * r4 + e, acc[db][kb][4 * r4 + e] * mul);
+          for (int i = 0; i < 16; ++i) {
+            const float val = acc[db][kb][i] * mul;
+            if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
+            else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
           }
-        }
-      }
     }
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }
