@@ -136,7 +136,10 @@ int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, i
  *   dV += P^T dO,  dP = dO V^T,  dS = P o (dP - delta),  dQ += scale dS K,  dK += scale dS^T Q,
  * dK/dV summed over the hq/hkv query heads of a KV head.  The three fp32 accumulators are
  * ADDED to (caller zeroes them before the first step): dq_acc [tq,hq,D], dk_acc, dv_acc
- * [tkv,hkv,D].  Accumulation uses fp32 atomics, so the summation order varies run to run.
+ * [tkv,hkv,D].  Rows (keys) that only one work item of the call touches are read, added to and
+ * written back with plain loads and stores; the others use fp32 atomics, so their summation
+ * order varies run to run.  While the call runs nobody else may write the accumulators.
+ * Limits: tq*hq*head_dim*2 and tkv*hkv*head_dim*2 below 2^31 bytes (FCP_ERR_UNSUPPORTED).
  * Other arguments as in fcp_attn_fwd_step; scratch sized with FCP_SCRATCH_BWD.
  */
 int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d_o,

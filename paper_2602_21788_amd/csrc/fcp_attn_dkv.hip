@@ -15,24 +15,26 @@
 //     128 registers, so that four waves fit a SIMD and the hardware interleaves them (a wave's own matrix and
 //     vector instructions hardly overlap on this chip; those of different waves of a SIMD do):
 //       P wave:  S = Q K^T, P = exp2(c S - LSE log2 e) with the mask; keeps the K fragments of its 32 keys; leaves
-//                P in LDS in bf16 B-operand form;
+//                P in LDS in bf16 operand form;
 //       dS wave: dP - delta = dO V^T with the accumulator started at -delta; keeps the V fragments of its 32
-//                keys; then, one step behind, dS = P o (dP - delta), left in LDS in bf16 B-operand form;
-//       dV wave: dV^T += dO^T P of the step before, for 64 channels x 64 keys (the keys of two P waves), so that
-//                every transposed dO fragment read from LDS feeds two matrix instructions;
-//       dK wave: dK^T += Q^T dS, two steps behind, 64 channels x 64 keys likewise;
+//                keys; then, one step behind, dS = P o (dP - delta), left in LDS in bf16 operand form;
+//       dV wave: dV += P^T dO, two steps behind, for 64 keys (those of two P waves) x 64 channels, so that every
+//                transposed dO fragment read from LDS feeds two matrix instructions; P is the A operand and the
+//                accumulator comes out as [key x channel] with the channel on the lane;
+//       dK wave: dK += dS^T Q, three steps behind, 64 keys x 64 channels likewise;
 //     one block barrier per step orders the hand-overs and the reuse of the LDS stages.  LDS bandwidth, not the
 //     matrix pipe, bounds this kernel (about 1 KB of fragments per matrix instruction when a fragment is used
 //     once), hence bf16 hand-overs and the 64 x 64 blocks of the accumulating waves;
 //   * Q, dO blocks (32 rows) and their row statistics stream through LDS in five stages (two steps ahead, two
 //     behind) filled by LDS-direct buffer loads, one tile instruction per wave and step; the tiles are
-//     chunk-permuted so that both the row reads (A operands of S and dP) and the transpose reads (A operands
-//     dO^T, Q^T of the accumulating contractions) run at the full LDS rate;
-//   * S and dP come out as [query x key] with the key on the lane, which is exactly the B-operand layout of
-//     dV^T += dO^T P and dK^T += Q^T dS: the hand-over is lane to same lane;
+//     chunk-permuted so that both the row reads (A operands of S and dP) and the transpose reads (B operands
+//     dO, Q of the accumulating contractions, one channel per lane) run at the full LDS rate;
+//   * S and dP come out as [query x key] with the key on the lane, which is exactly the A-operand layout of
+//     P^T and dS^T in dV += P^T dO and dK += dS^T Q: the hand-over is lane to same lane;
 //   * inside the matrix phases every LDS fragment is requested several MFMAs before its use;
-//   * the result is added to the caller's fp32 accumulators once per unit: with plain load-add-store when the
-//     scheduler found that no other item of the launch touches the same keys, otherwise with fp32 atomics.
+//   * the caller's fp32 accumulators: when the scheduler found that no other item of the launch touches the tile's
+//     keys, the waves' accumulators start from the caller's values and the epilogue stores whole 128-byte lines;
+//     otherwise they start at zero and the epilogue adds with fp32 atomics.
 #include "fcp_bwd.h"
 
 namespace fcp {
