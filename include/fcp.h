@@ -152,6 +152,44 @@ int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d
 /* Cast n fp32 accumulator values to bf16, round to nearest even.  Device pointers. */
 int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, void* stream);
 
+/* Coefficients of the scheduler's time model (paper Eq. 8-9), all >= 0, in the caller's time unit. */
+typedef struct fcp_cost_model {
+  double alpha1;         /* attention compute per (1 + eta_k) |s_k|^2                         */
+  double alpha2;         /* linear-layer compute per token                                     */
+  double beta1;          /* constant compute overhead of a group                               */
+  double alpha3_over_v;  /* KV exchange per token: alpha3 / v_p, one link speed for all groups */
+  double beta2;          /* constant exchange overhead of a group with a ring (degree > 1)     */
+} fcp_cost_model;
+
+/*
+ * fcp_plan_groups -- HOST ONLY.  The scheduler's two stages (paper Sec. 4.4) for one micro-batch:
+ *  1. atomic sequence groups by best-fit decreasing: sequences in decreasing length (equal lengths in
+ *     input order); each goes into the open group with the least remaining room that still holds it
+ *     (the group opened first among equals), otherwise it opens a group of
+ *     d_min = ceil(len / tokens_per_rank) ranks and d_min * tokens_per_rank tokens;
+ *  2. the 2D dynamic programme of Eq. 11 / Alg. 1 over (groups, ranks): every group gets a degree
+ *     d >= d_min, at most n_ranks in total (Cond. 6), so that the largest group time is least; among
+ *     equal makespans the fewest ranks, and inside the recurrence the smallest degree, win.
+ * Group time at degree d (Eq. 8-10; the compute terms divided by d, no exchange at d = 1, the exchange
+ * hidden behind the attention compute as far as it goes):
+ *   T_cpa = sum_k alpha1 (1 + eta_k) len_k^2 / d,   T_cp = T_cpa + sum_k alpha2 len_k / d + beta1,
+ *   T_cm = d == 1 ? 0 : alpha3_over_v * sum_k len_k + beta2,   T = T_cp + T_cm - min(T_cpa, T_cm).
+ * tokens_per_rank = (E - M_ms) / M_token of Cond. 3 / Eq. 7: a rank's activation budget in tokens.
+ *   seq_lens [n_seqs] host, >= 1;  eta [n_seqs] host or NULL (all 0: causal masks), >= 0
+ *   group_of_seq [n_seqs] out: group index (in order of opening) of every sequence
+ *   n_groups out;  group_d_min, group_degree, group_base_rank: out arrays of at least n_seqs entries,
+ *   the first n_groups are written; base ranks are the running sums of the degrees
+ *   makespan out: the largest group time of the plan
+ * A sequence of a group runs at the group's degree on ranks base .. base + degree - 1 (the paper's atomic
+ * groups); cp_degree / base_rank for fcp_shard_plan follow from group_of_seq.
+ * Returns FCP_ERR_CAPACITY if the minimum degrees do not fit n_ranks (n_groups and group_d_min are valid
+ * then unless a single sequence alone needs more than n_ranks).
+ */
+int fcp_plan_groups(const int32_t* seq_lens, const float* eta, int32_t n_seqs, int32_t n_ranks,
+                    int64_t tokens_per_rank, const fcp_cost_model* cm, int32_t* group_of_seq,
+                    int32_t* n_groups, int32_t* group_d_min, int32_t* group_degree,
+                    int32_t* group_base_rank, double* makespan);
+
 /*
  * Reads back what the last fwd/bwd step that used `scratch` recorded: the number of
  * scheduled tiles and the number of rejected work items.  Synchronises `stream`.

@@ -4,6 +4,6 @@ The product is libfcp.so (C ABI in include/fcp.h, HIP kernels under csrc/); `bin
 exposes the same entry points to Python and `rank` wires them into one rank's
 forward / backward pass for tests and benchmarks.
 """
-from .binding import (FcpError, fcp_attn_bwd_delta, fcp_attn_bwd_step, fcp_attn_fwd_step,  # noqa: F401
-                      fcp_grad_finalize, fcp_lse_merge, fcp_scratch_bytes, fcp_scratch_status,
+from .binding import (CostModel, FcpError, fcp_attn_bwd_delta, fcp_attn_bwd_step, fcp_attn_fwd_step,  # noqa: F401
+                      fcp_grad_finalize, fcp_lse_merge, fcp_plan_groups, fcp_scratch_bytes, fcp_scratch_status,
                       fcp_shard_plan)

@@ -24,7 +24,7 @@ WORK_DTYPE = np.dtype([("seq", "<i4"), ("rank", "<i4"), ("step", "<i4"),
                        ("q_local_off", "<i4"), ("q_seq_start", "<i4"), ("q_len", "<i4"),
                        ("n_seg", "<i4"), ("k_seq_start", "<i4", (2,)), ("k_len", "<i4", (2,))])
 
-EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
+EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_plan_groups", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
            "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status"]
 
 
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
         L.fcp_last_error.argtypes = []
         L.fcp_shard_plan.restype = ctypes.c_int
         L.fcp_shard_plan.argtypes = [P, P, P, I32, P, I64, P, P, I64, P]
+        L.fcp_plan_groups.restype = ctypes.c_int
+        L.fcp_plan_groups.argtypes = [P, P, I32, I32, I64, P, P, P, P, P, P, P]
         L.fcp_scratch_bytes.restype = SZ
         L.fcp_scratch_bytes.argtypes = [ctypes.c_int, I32, I32, I32, I32, I32, I64, I32]
         L.fcp_attn_fwd_step.restype = ctypes.c_int
@@ -111,6 +113,34 @@ def fcp_shard_plan(seq_lens, cp_degree, base_rank=None):
     _check(lib().fcp_shard_plan(_np_ptr(sl), _np_ptr(cd), _np_ptr(br), len(sl), _np_ptr(chunks), nc.value,
                                 ctypes.byref(nc), _np_ptr(work), nw.value, ctypes.byref(nw)))
     return chunks, work
+
+
+class CostModel(ctypes.Structure):
+    """fcp_cost_model: coefficients of the scheduler's time model (Eq. 8-9)."""
+    _fields_ = [("alpha1", ctypes.c_double), ("alpha2", ctypes.c_double), ("beta1", ctypes.c_double),
+                ("alpha3_over_v", ctypes.c_double), ("beta2", ctypes.c_double)]
+
+
+def fcp_plan_groups(seq_lens, n_ranks, tokens_per_rank, cost_model, eta=None):
+    """Host only.  Returns dict(group_of_seq, d_min, degree, base_rank, makespan); raises FcpError (capacity) if
+    the groups' minimum degrees do not fit n_ranks.  cost_model: CostModel or a 5-tuple in its field order."""
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    if sl.ndim != 1:
+        raise ValueError("seq_lens must be 1-D")
+    et = None if eta is None else np.ascontiguousarray(eta, dtype=np.float32)
+    if et is not None and et.shape != sl.shape:
+        raise ValueError("eta must match seq_lens")
+    cm = cost_model if isinstance(cost_model, CostModel) else CostModel(*[float(x) for x in cost_model])
+    k = len(sl)
+    group_of = np.zeros(k, np.int32)
+    d_min, degree, base = (np.zeros(max(k, 1), np.int32) for _ in range(3))
+    ng, mk = ctypes.c_int32(0), ctypes.c_double(0.0)
+    _check(lib().fcp_plan_groups(_np_ptr(sl), _np_ptr(et), k, int(n_ranks), int(tokens_per_rank), ctypes.byref(cm),
+                                 _np_ptr(group_of), ctypes.byref(ng), _np_ptr(d_min), _np_ptr(degree), _np_ptr(base),
+                                 ctypes.byref(mk)))
+    n = ng.value
+    return {"group_of_seq": group_of, "d_min": d_min[:n].copy(), "degree": degree[:n].copy(),
+            "base_rank": base[:n].copy(), "makespan": mk.value}
 
 
 def fcp_scratch_bytes(which, tq, tkv, hq, hkv, head_dim, n_work, n_parts) -> int:

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libfcp.so")
-SOURCES = ["fcp_host.cpp", "fcp_sched.hip", "fcp_rowops.hip", "fcp_attn_fwd.hip", "fcp_attn_dkv.hip", "fcp_attn_bwd.hip"]
+SOURCES = ["fcp_host.cpp", "fcp_planner.cpp", "fcp_sched.hip", "fcp_rowops.hip", "fcp_attn_fwd.hip", "fcp_attn_dkv.hip", "fcp_attn_bwd.hip"]
 HEADERS = [os.path.join(CSRC, "fcp_internal.h"), os.path.join(CSRC, "fcp_device.h"), os.path.join(CSRC, "fcp_bwd.h"),
            os.path.join(ROOT, "include", "fcp.h")]
 # packed fp32 VALU ops are switched off for all device code (see the note in the package docs)

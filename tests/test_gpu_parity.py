@@ -120,3 +120,18 @@ def test_cfg2_full_size_sampled():
              "dK": rel_err(dK[:, kvh:kvh + 1], dK_ref), "dV": rel_err(dV[:, kvh:kvh + 1], dV_ref)}
         _say(f"  kv head {kvh}: {e}")
         assert e["dK"] <= TOL_BF16_REL and e["dV"] <= TOL_BF16_REL
+
+
+def test_profiler_fits_measured_attention_times():
+    """The scheduler's Profiler on this library's own kernels: fit Eq. 8's compute model to measured forward + backward
+    times of single sequences and plan a micro-batch with it (the paper reports estimation errors below 8 %; the
+    bound here is loose because short sequences are launch-bound)."""
+    from paper_2602_21788_amd import profiler
+    import paper_2602_21788_amd as fcp
+    lens = [2048, 4096, 8192, 12288, 16384]
+    times = profiler.profile_attention(lens, [1] * len(lens))
+    (a1, a2, b1), err = profiler.fit_compute_coefficients(lens, [1] * len(lens), times)
+    _say(f"profiler: times {['%.3f ms' % (t * 1e3) for t in times]} alpha1 {a1:.3e} alpha2 {a2:.3e} beta1 {b1:.3e} max rel err {err:.3f}")
+    assert a1 > 0 and err < 0.25
+    plan = fcp.fcp_plan_groups([16384, 4096, 4096, 2048], 8, 8192, (a1, max(a2, 0.0), max(b1, 0.0), 0.0, 0.0))
+    assert plan["d_min"][0] == 2 and plan["degree"][0] >= plan["degree"][1] and sum(plan["degree"]) <= 8
