@@ -19,10 +19,11 @@
 //   * scores are computed TRANSPOSED, S^T = K Q^T with v_mfma_f32_32x32x16_bf16: a lane then
 //     holds 16 keys of ONE query column, so the row maximum and sum are in-lane reductions
 //     plus a single exchange with the lane 32 away, and the exponentiated scores are already
-//     in the B-operand layout of the second contraction O^T += V^T P^T;
+//     in the A-operand layout of the second contraction O += P V, whose accumulator is then
+//     [query x channel] with the channel on the lane: the epilogue stores whole 128-byte lines;
 //   * PING-PONG: waves w and w+4 share a SIMD (measured).  Matrix and vector instructions of
 //     DIFFERENT waves of a SIMD execute together almost perfectly, those of one wave hardly do.
-//     Each wave therefore alternates a matrix slot (scores of tile t, O^T += V^T P^T of tile t-1)
+//     Each wave therefore alternates a matrix slot (scores of tile t, O += P V of tile t-1)
 //     with a vector slot (mask, maximum, exponentials, sum, conversion of tile t), and waves 4..7
 //     run one slot behind waves 0..3; a block barrier at every slot boundary keeps the two
 //     halves in opposite slots, so a SIMD's matrix pipe is busy in every slot;
@@ -83,6 +84,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
   __shared__ int32_t s_next_unit;
   __shared__ int32_t s_rec[16];
+  __shared__ __attribute__((aligned(16))) float s_rowf[8][32];   // per wave: one factor per query row, see scale_rows()
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -111,7 +113,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
   int kaddr[C::NKA];
 #pragma unroll
   for (int j = 0; j < C::NKA; ++j) kaddr[j] = tile_off<KT>(l32, 2 * j + g2);
-  // V^T fragments (A operand of O^T += V^T P^T, rows d = 32 db + l32; k-slots = keys 16 tt + {4 g2 + [0,4),
+  // V^T fragments (B operand of O += P V, columns d = 32 db + l32; k-slots = keys 16 tt + {4 g2 + [0,4),
   // 8 + 4 g2 + [0,4)}).  Transpose read: inside a 16-lane block lane i supplies the address of key row
   // (i / 4), channels 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for key group b / 2.
   int vaddr[C::NVA];
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       const int tt = g / C::NVA, db = g % C::NVA;
       return tr_read_8(smem + va[db] + tt * (16 * VT::row_base(1)), 8 * VT::row_base(1));
     };
-    // Matrix slot of step `it`: scores of tile it (if DO_S), O^T += V^T P^T of tile it - 1 (if DO_PV).  The order
+    // Matrix slot of step `it`: scores of tile it (if DO_S), O += P V of tile it - 1 (if DO_PV).  The order
     // is written out MFMA by MFMA and fenced so that every LDS fragment is requested kAhead MFMAs before the
     // one that consumes it.
     auto matrix_slot = [&](auto do_s_c, auto do_pv_c, int it) {
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
           sacc[x / C::NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], qf[x % C::NS], x % C::NS == 0 ? zero16() : sacc[x / C::NS], 0, 0, 0);
         } else {
           const int g = x - N1;
-          oacc[g % C::NVA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], pf[g / C::NVA], oacc[g % C::NVA], 0, 0, 0);
+          oacc[g % C::NVA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[g / C::NVA], fr[x], oacc[g % C::NVA], 0, 0, 0);
         }
         request(x + kAhead);
         __builtin_amdgcn_sched_barrier(0);
@@ -267,6 +269,21 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     // by 2^kRescaleThreshold, until then probabilities may exceed 1 by at most that factor), exponentials, row
     // sum, conversion to bf16.  The row sum is taken over the unrounded fp32 values (summing the bf16-rounded
     // ones would cost up to 2^-9 relative on a peaked row, more than the 1e-3 the LSE has to hold).
+    // O is accumulated as [query x channel] with the channel on the lane (register i = row 8 (i/4) + 4 g2 + i%4 of the
+    // wave's 32), so that the epilogue stores whole 128-byte lines; the row statistics live one row per lane.  A
+    // per-row factor therefore goes through the wave's LDS slot: every lane leaves its row's factor, then picks up
+    // the four factors of each of its register groups.  (Rare: the rescale is lazy.)
+    auto scale_rows = [&](float f) {
+      s_rowf[wave][l32] = f;                       // both half-waves hold the same value for a row
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(&s_rowf[wave][8 * j + 4 * g2]);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) oacc[db][4 * j + e] *= a[e];
+      }
+    };
     auto vector_slot = [&](int it) {
       int k_pos0, n_valid;
       tile_geom(it, k_pos0, n_valid);
@@ -288,10 +305,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
         const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
         m_run = m_new;
         l_run *= alpha;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        scale_rows(alpha);
       }
       const float m_use = m_run == -INFINITY ? 0.f : m_run;
       float psum = 0.f;
@@ -340,21 +354,29 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     // ---- epilogue: normalise, write partial O (fp32) and LSE --------------------------------
     const float l_tot = lane32_partner_sum(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (row_valid) {
-      float* orow = p.o_part + (int64_t)t.step * ((int64_t)p.tq * p.hq * D) +
-                    ((int64_t)(t.q_row0 + my_row) * p.hq + head) * D;
+    scale_rows(inv);
+    {
+      // The rows are reached through a buffer resource that ends with the tile's last row (stores past it are
+      // dropped): per-lane offset = the lane's part (row 4 g2 of a group of eight, channel l32), scalar offset =
+      // the rest.  A store instruction covers two whole 128-byte lines.
+      const int row_bytes = p.hq * D * 4;
+      const int n_wave_rows = t.rows - wave_r0;
+      const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(p.o_part + (int64_t)t.step * ((int64_t)p.tq * p.hq * D) + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D),
+          (short)0, n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 4 : 0, 0x00020000);
+      const int o_voff = 4 * g2 * row_bytes + 4 * l32;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          f32x4 o4 = {oacc[db][4 * r4] * inv, oacc[db][4 * r4 + 1] * inv, oacc[db][4 * r4 + 2] * inv,
-                      oacc[db][4 * r4 + 3] * inv};
-          *reinterpret_cast<f32x4*>(orow + 32 * db + 8 * r4 + 4 * g2) = o4;
+        for (int i = 0; i < 16; ++i) {
+          const float val = oacc[db][i];   // (a bit cast applied to the vector element itself reads element 0)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), ro, o_voff,
+                                                (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db, 0);
         }
-      if (g2 == 0) {
-        const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-        p.lse_part[(int64_t)t.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
-      }
+    }
+    if (row_valid && g2 == 0) {
+      const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+      p.lse_part[(int64_t)t.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
     }
     uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block (barrier: LDS stages are free)
   }
