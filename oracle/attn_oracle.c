@@ -1,5 +1,5 @@
 /*
- * CPU oracle for exact causal softmax attention and its gradients.
+ * CPU oracle for exact softmax attention (causal, or causal with full-attention spans) and its gradients.
  *
  * TEST INFRASTRUCTURE ONLY.  Nothing in the product path may call, link or load
  * this file; it exists to check the HIP kernels and to serve as the timed CPU
@@ -10,7 +10,12 @@
  *
  *   paper Eq. 1 (Sec. 3.1):  Attn(Q,K,V) = softmax(Q K^T / sqrt(d_k)) V
  *   paper Sec. 4.3:          language models use the causal mask, i.e. query i of a
- *                            sequence sees keys j <= i of the same sequence only.
+ *                            sequence sees keys j <= i of the same sequence only;
+ *   paper Sec. 4.3 (time estimation, before Eq. 8): multimodal models give SOME tokens full
+ *                            attention.  Reading: tokens are marked with a span id (span_id[t] >= 0,
+ *                            -1 = unmarked); two tokens of one sequence with the same span id see each
+ *                            other in both directions, every other pair is causal.  span_id == NULL
+ *                            is the plain causal mask.
  *
  * Inputs are bf16 bit patterns (uint16), widened exactly to double; every sum is
  * carried in double.  Layouts: Q, dO [T, Hq, D]; K, V [T, Hkv, D]; T = all packed
@@ -57,6 +62,12 @@ static int seq_of(const int32_t* cu, int n_seqs, int64_t t) {
   return lo;
 }
 
+/* the mask, by definition: i, j are positions inside the sequence that starts at global token t0 */
+static int visible(const int32_t* span_id, int64_t t0, int64_t i, int64_t j) {
+  if (j <= i) return 1;
+  return span_id && span_id[t0 + i] >= 0 && span_id[t0 + i] == span_id[t0 + j];
+}
+
 static double dot_bf(const uint16_t* a, const uint16_t* b, int D) {
   double s = 0.0;
   for (int c = 0; c < D; ++c) s += bf(a[c]) * bf(b[c]);
@@ -66,7 +77,7 @@ static double dot_bf(const uint16_t* a, const uint16_t* b, int D) {
 /* O [n_rows, Hq, D] and LSE [n_rows, Hq] (row-major in the order of `rows`). */
 void oracle_attn_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* v,
                      const int32_t* cu_seqlens, int n_seqs, int hq, int hkv, int D,
-                     double scale, const int64_t* rows, int64_t n_rows,
+                     double scale, const int32_t* span_id, const int64_t* rows, int64_t n_rows,
                      double* O, double* LSE) {
   const int G = hq / hkv;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
@@ -75,20 +86,24 @@ void oracle_attn_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* v,
       const int64_t t = rows[r];
       const int n = seq_of(cu_seqlens, n_seqs, t);
       const int64_t t0 = cu_seqlens[n];
+      const int64_t L = cu_seqlens[n + 1] - t0;
       const int64_t i = t - t0;
       const int g = h / G;
       const uint16_t* qi = q + (t * hq + h) * (int64_t)D;
-      double* s = (double*)malloc(sizeof(double) * (size_t)(i + 1));
+      double* s = (double*)malloc(sizeof(double) * (size_t)L);
       double m = -INFINITY;
-      for (int64_t j = 0; j <= i; ++j) {
+      for (int64_t j = 0; j < L; ++j) {
+        if (!visible(span_id, t0, i, j)) continue;
         s[j] = scale * dot_bf(qi, k + ((t0 + j) * hkv + g) * (int64_t)D, D);
         if (s[j] > m) m = s[j];
       }
       double l = 0.0;
-      for (int64_t j = 0; j <= i; ++j) l += exp(s[j] - m);
+      for (int64_t j = 0; j < L; ++j)
+        if (visible(span_id, t0, i, j)) l += exp(s[j] - m);
       double* o = O + (r * hq + h) * (int64_t)D;
       for (int c = 0; c < D; ++c) o[c] = 0.0;
-      for (int64_t j = 0; j <= i; ++j) {
+      for (int64_t j = 0; j < L; ++j) {
+        if (!visible(span_id, t0, i, j)) continue;
         const double p = exp(s[j] - m) / l;
         const uint16_t* vj = v + ((t0 + j) * hkv + g) * (int64_t)D;
         for (int c = 0; c < D; ++c) o[c] += p * bf(vj[c]);
@@ -102,7 +117,7 @@ void oracle_attn_fwd(const uint16_t* q, const uint16_t* k, const uint16_t* v,
 /* dQ [n_rows, Hq, D].  O, LSE are the oracle's own forward results for the same rows. */
 void oracle_attn_dq(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* d_o,
                     const int32_t* cu_seqlens, int n_seqs, int hq, int hkv, int D,
-                    double scale, const int64_t* rows, int64_t n_rows,
+                    double scale, const int32_t* span_id, const int64_t* rows, int64_t n_rows,
                     const double* O, const double* LSE, double* dQ) {
   const int G = hq / hkv;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
@@ -111,6 +126,7 @@ void oracle_attn_dq(const uint16_t* q, const uint16_t* k, const uint16_t* v, con
       const int64_t t = rows[r];
       const int n = seq_of(cu_seqlens, n_seqs, t);
       const int64_t t0 = cu_seqlens[n];
+      const int64_t L = cu_seqlens[n + 1] - t0;
       const int64_t i = t - t0;
       const int g = h / G;
       const uint16_t* qi = q + (t * hq + h) * (int64_t)D;
@@ -120,7 +136,8 @@ void oracle_attn_dq(const uint16_t* q, const uint16_t* k, const uint16_t* v, con
       for (int c = 0; c < D; ++c) delta += bf(doi[c]) * oi[c];
       double* dq = dQ + (r * hq + h) * (int64_t)D;
       for (int c = 0; c < D; ++c) dq[c] = 0.0;
-      for (int64_t j = 0; j <= i; ++j) {
+      for (int64_t j = 0; j < L; ++j) {
+        if (!visible(span_id, t0, i, j)) continue;
         const uint16_t* kj = k + ((t0 + j) * hkv + g) * (int64_t)D;
         const uint16_t* vj = v + ((t0 + j) * hkv + g) * (int64_t)D;
         const double p = exp(scale * dot_bf(qi, kj, D) - LSE[r * hq + h]);
@@ -137,7 +154,7 @@ void oracle_attn_dq(const uint16_t* q, const uint16_t* k, const uint16_t* v, con
  * output element has a single writer. */
 void oracle_attn_dkv(const uint16_t* q, const uint16_t* k, const uint16_t* v, const uint16_t* d_o,
                      const int32_t* cu_seqlens, int n_seqs, int64_t T, int hq, int hkv, int D,
-                     double scale, const int64_t* rows, int64_t n_rows,
+                     double scale, const int32_t* span_id, const int64_t* rows, int64_t n_rows,
                      const double* O, const double* LSE, const int64_t* keys, int64_t n_keys,
                      double* dK, double* dV) {
   const int G = hq / hkv;
@@ -156,7 +173,7 @@ void oracle_attn_dkv(const uint16_t* q, const uint16_t* k, const uint16_t* v, co
   for (int64_t kidx = 0; kidx < n_keys; ++kidx) {
     const int64_t tj = keys ? keys[kidx] : kidx;
     const int n = seq_of(cu_seqlens, n_seqs, tj);
-    const int64_t t1 = cu_seqlens[n + 1];
+    const int64_t t0 = cu_seqlens[n], t1 = cu_seqlens[n + 1];
     for (int g = 0; g < hkv; ++g) {
       double* dk = dK + (kidx * hkv + g) * (int64_t)D;
       double* dv = dV + (kidx * hkv + g) * (int64_t)D;
@@ -164,7 +181,7 @@ void oracle_attn_dkv(const uint16_t* q, const uint16_t* k, const uint16_t* v, co
     }
     for (int64_t r = 0; r < n_rows; ++r) {
       const int64_t ti = rows[r];
-      if (ti < tj || ti >= t1) continue;          /* same sequence and key j <= query i */
+      if (ti < t0 || ti >= t1 || !visible(span_id, t0, ti - t0, tj - t0)) continue;   /* same sequence, key seen */
       for (int h = 0; h < hq; ++h) {
         const int g = h / G;
         const uint16_t* kj = k + (tj * hkv + g) * (int64_t)D;
