@@ -57,7 +57,8 @@ typedef struct fcp_chunk_desc {
 
 /* One per (rank, ring step, sequence, query chunk) that sees at least one key.  44 bytes.
  * The mask is implied by positions: a key is visible iff k_pos <= q_pos, where
- * q_pos = q_seq_start + row and k_pos = k_seq_start[s] + key inside segment s.
+ * q_pos = q_seq_start + row and k_pos = k_seq_start[s] + key inside segment s (with full-attention spans:
+ * iff k_pos <= limit(q_pos), see fcp_shard_plan_mixed).
  * Sorted by (rank, step, seq, q_seq_start).  Unused segment fields are 0. */
 typedef struct fcp_work_desc {
   int32_t seq, rank, step;      /* step s reads the KV chunks of group-local rank (i - s) mod d;
@@ -148,6 +149,71 @@ int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d
                       int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
                       float softmax_scale, float* dq_acc, float* dk_acc, float* dv_acc,
                       void* scratch, size_t scratch_bytes, void* stream);
+
+/*
+ * Mixed masks (paper Sec. 4.3, time estimation before Eq. 8: multimodal models give some tokens full
+ * attention; the mask efficiency factor eta_k of Eq. 8 follows from the shape of the mask).  Reading: the
+ * tokens [start, start + len) of a span see each other in BOTH directions, every other pair of a sequence is
+ * causal.  Such a mask keeps two monotone properties the kernels use: the query at position i sees exactly
+ * the keys 0 .. limit(i), and the key at position j is seen by exactly the queries from(j) .. L-1, where
+ * limit / from are the position itself outside a span and the span's last / first position inside one.
+ */
+typedef struct fcp_span {
+  int32_t seq;    /* index into seq_lens          */
+  int32_t start;  /* first token of the span      */
+  int32_t len;    /* tokens in the span, >= 1     */
+} fcp_span;
+
+/*
+ * fcp_shard_plan_mixed -- fcp_shard_plan for sequences with full-attention spans.  HOST ONLY, integer exact.
+ * The chunks are those of fcp_shard_plan; a work item lists every key chunk of its ring step of which the
+ * query chunk's last row sees at least the first key, which may include a LATER chunk when a span crosses the
+ * chunk border.  The work descriptors keep their meaning, except that inside a (query row, segment) pair a key
+ * is visible iff k_pos <= limit(q_pos) instead of k_pos <= q_pos.
+ *   spans [n_spans] host, sorted by (seq, start), not overlapping, inside their sequences (else
+ *   FCP_ERR_INVALID_ARG); n_spans = 0 gives fcp_shard_plan's result.  Other arguments as in fcp_shard_plan.
+ */
+int fcp_shard_plan_mixed(const int32_t* seq_lens, const int32_t* cp_degree, const int32_t* base_rank,
+                         int32_t n_seqs, const fcp_span* spans, int32_t n_spans, fcp_chunk_desc* chunks,
+                         int64_t chunk_cap, int64_t* n_chunks, fcp_work_desc* work, int64_t work_cap,
+                         int64_t* n_work);
+
+/*
+ * fcp_mask_tables -- HOST ONLY, integer exact.  The per-row form of a mixed mask for one rank:
+ *   q_limit [n_q] out (or NULL): for every local query row of `rank` (rows as laid out by the chunk table,
+ *            n_q = the rank's row count, written to *n_q if non-NULL) the sequence position of the last key
+ *            the row sees; q_limit_cap = entries available (FCP_ERR_CAPACITY if fewer than n_q)
+ *   k_from  [sum of seq_lens] out (or NULL): for every row of the KV pool the sequence position of the first
+ *            query that sees the key
+ *   eta     [n_seqs] out (or NULL): visible pairs of the sequence over its causal count L (L + 1) / 2, minus 1
+ *            (the factor of Eq. 8; feeds fcp_plan_groups)
+ *   chunks [n_chunks]: the chunk table of fcp_shard_plan(_mixed) for the same lengths; spans as above.
+ */
+int fcp_mask_tables(const int32_t* seq_lens, int32_t n_seqs, const fcp_span* spans, int32_t n_spans,
+                    const fcp_chunk_desc* chunks, int64_t n_chunks, int32_t rank, int32_t* q_limit,
+                    int64_t q_limit_cap, int64_t* n_q, int32_t* k_from, float* eta);
+
+/*
+ * fcp_attn_fwd_step_mixed / fcp_attn_bwd_step_mixed -- the two attention steps under a mixed mask.  As
+ * fcp_attn_fwd_step / fcp_attn_bwd_step with the work items of fcp_shard_plan_mixed and
+ *   q_limit [tq]  int32 device: fcp_mask_tables' q_limit of this rank
+ *   k_from  [tkv] int32 device: fcp_mask_tables' k_from (backward only)
+ * Both tables must be non-decreasing along a chunk / a sequence and describe the same mask; values are only
+ * compared with positions, never used as addresses, so wrong tables give wrong numbers but no access outside
+ * the given extents.
+ */
+int fcp_attn_fwd_step_mixed(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                            int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                            int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                            float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part,
+                            void* scratch, size_t scratch_bytes, void* stream);
+int fcp_attn_bwd_step_mixed(const void* q, const void* k, const void* v, const void* d_o,
+                            const float* lse, const float* delta, const int32_t* cu_seqlens_kv,
+                            int32_t n_seqs, const fcp_work_desc* work, int64_t n_work,
+                            int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                            float softmax_scale, const int32_t* q_limit, const int32_t* k_from,
+                            float* dq_acc, float* dk_acc, float* dv_acc,
+                            void* scratch, size_t scratch_bytes, void* stream);
 
 /* Cast n fp32 accumulator values to bf16, round to nearest even.  Device pointers. */
 int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, void* stream);

@@ -23,9 +23,11 @@ CHUNK_DTYPE = np.dtype([("seq", "<i4"), ("rank", "<i4"), ("chunk", "<i4"),
 WORK_DTYPE = np.dtype([("seq", "<i4"), ("rank", "<i4"), ("step", "<i4"),
                        ("q_local_off", "<i4"), ("q_seq_start", "<i4"), ("q_len", "<i4"),
                        ("n_seg", "<i4"), ("k_seq_start", "<i4", (2,)), ("k_len", "<i4", (2,))])
+SPAN_DTYPE = np.dtype([("seq", "<i4"), ("start", "<i4"), ("len", "<i4")])
 
 EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_plan_groups", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
-           "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status"]
+           "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status",
+           "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed"]
 
 
 class FcpError(RuntimeError):
@@ -66,6 +68,15 @@ def lib() -> ctypes.CDLL:
         L.fcp_grad_finalize.argtypes = [P, P, I64, P]
         L.fcp_scratch_status.restype = ctypes.c_int
         L.fcp_scratch_status.argtypes = [P, P, P, P]
+        L.fcp_shard_plan_mixed.restype = ctypes.c_int
+        L.fcp_shard_plan_mixed.argtypes = [P, P, P, I32, P, I32, P, I64, P, P, I64, P]
+        L.fcp_mask_tables.restype = ctypes.c_int
+        L.fcp_mask_tables.argtypes = [P, I32, P, I32, P, I64, I32, P, I64, P, P, P]
+        L.fcp_attn_fwd_step_mixed.restype = ctypes.c_int
+        L.fcp_attn_fwd_step_mixed.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, I32, F, P, P, P, P, SZ, P]
+        L.fcp_attn_bwd_step_mixed.restype = ctypes.c_int
+        L.fcp_attn_bwd_step_mixed.argtypes = [P, P, P, P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, F, P, P, P, P, P, P,
+                                              SZ, P]
         _lib = L
     return _lib
 
@@ -115,6 +126,56 @@ def fcp_shard_plan(seq_lens, cp_degree, base_rank=None):
     return chunks, work
 
 
+def _spans(spans):
+    """list of (seq, start, len) or a SPAN_DTYPE array -> contiguous SPAN_DTYPE array (order kept: the library
+    checks it)"""
+    if isinstance(spans, np.ndarray) and spans.dtype == SPAN_DTYPE:
+        return np.ascontiguousarray(spans)
+    a = np.zeros(len(spans), SPAN_DTYPE)
+    for i, (k, st, ln) in enumerate(spans):
+        a[i] = (k, st, ln)
+    return a
+
+
+def fcp_shard_plan_mixed(seq_lens, cp_degree, spans, base_rank=None):
+    """Host only.  fcp_shard_plan for sequences with full-attention spans [(seq, start, len), ...]."""
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    cd = np.ascontiguousarray(cp_degree, dtype=np.int32)
+    if sl.shape != cd.shape or sl.ndim != 1:
+        raise ValueError("seq_lens and cp_degree must be 1-D and the same length")
+    br = None if base_rank is None else np.ascontiguousarray(base_rank, dtype=np.int32)
+    if br is not None and br.shape != sl.shape:
+        raise ValueError("base_rank must match seq_lens")
+    sp = _spans(spans)
+    nc, nw = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().fcp_shard_plan_mixed(_np_ptr(sl), _np_ptr(cd), _np_ptr(br), len(sl), _np_ptr(sp), len(sp), None, 0,
+                                      ctypes.byref(nc), None, 0, ctypes.byref(nw)))
+    chunks = np.zeros(nc.value, CHUNK_DTYPE)
+    work = np.zeros(nw.value, WORK_DTYPE)
+    _check(lib().fcp_shard_plan_mixed(_np_ptr(sl), _np_ptr(cd), _np_ptr(br), len(sl), _np_ptr(sp), len(sp),
+                                      _np_ptr(chunks), nc.value, ctypes.byref(nc), _np_ptr(work), nw.value,
+                                      ctypes.byref(nw)))
+    return chunks, work
+
+
+def fcp_mask_tables(seq_lens, spans, chunks, rank):
+    """Host only.  Returns (q_limit [tq of rank] int32, k_from [sum of seq_lens] int32, eta [n_seqs] float32)."""
+    sl = np.ascontiguousarray(seq_lens, dtype=np.int32)
+    sp = _spans(spans)
+    ch = np.ascontiguousarray(chunks)
+    if ch.dtype != CHUNK_DTYPE:
+        raise ValueError("chunks must be a CHUNK_DTYPE array")
+    nq = ctypes.c_int64(0)
+    _check(lib().fcp_mask_tables(_np_ptr(sl), len(sl), _np_ptr(sp), len(sp), _np_ptr(ch), len(ch), int(rank), None, 0,
+                                 ctypes.byref(nq), None, None))
+    q_limit = np.zeros(nq.value, np.int32)
+    k_from = np.zeros(int(sl.sum()), np.int32)
+    eta = np.zeros(len(sl), np.float32)
+    _check(lib().fcp_mask_tables(_np_ptr(sl), len(sl), _np_ptr(sp), len(sp), _np_ptr(ch), len(ch), int(rank),
+                                 _np_ptr(q_limit), len(q_limit), ctypes.byref(nq), _np_ptr(k_from), _np_ptr(eta)))
+    return q_limit, k_from, eta
+
+
 class CostModel(ctypes.Structure):
     """fcp_cost_model: coefficients of the scheduler's time model (Eq. 8-9)."""
     _fields_ = [("alpha1", ctypes.c_double), ("alpha2", ctypes.c_double), ("beta1", ctypes.c_double),
@@ -159,6 +220,20 @@ def fcp_attn_fwd_step(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, o_pa
                                    scratch.numel() * scratch.element_size(), _stream(stream)))
 
 
+def fcp_attn_fwd_step_mixed(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, q_limit, o_part, lse_part, scratch,
+                            stream=None):
+    """fcp_attn_fwd_step under a mixed mask; q_limit: int32 device tensor [tq]."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    if q_limit.numel() != tq:
+        raise ValueError("q_limit must have one entry per local query row")
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_fwd_step_mixed(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(cu_seqlens_kv),
+                                         cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, n_parts, tq, tkv, hq, hkv, D,
+                                         float(softmax_scale), _dev_ptr(q_limit), _dev_ptr(o_part), _dev_ptr(lse_part),
+                                         _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
 def fcp_lse_merge(o_part, lse_part, o, lse, stream=None):
     n_parts, tq, hq, D = o_part.shape
     _check(lib().fcp_lse_merge(_dev_ptr(o_part), _dev_ptr(lse_part), n_parts, tq, hq, D, _dev_ptr(o), _dev_ptr(lse),
@@ -179,6 +254,22 @@ def fcp_attn_bwd_step(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softmax_sca
                                    _dev_ptr(cu_seqlens_kv), cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, tq, tkv,
                                    hq, hkv, D, float(softmax_scale), _dev_ptr(dq_acc), _dev_ptr(dk_acc), _dev_ptr(dv_acc),
                                    _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_attn_bwd_step_mixed(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softmax_scale, q_limit, k_from, dq_acc, dk_acc,
+                            dv_acc, scratch, stream=None):
+    """fcp_attn_bwd_step under a mixed mask; q_limit [tq], k_from [tkv]: int32 device tensors."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    if q_limit.numel() != tq or k_from.numel() != tkv:
+        raise ValueError("q_limit / k_from must have one entry per local query row / pool row")
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_bwd_step_mixed(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(d_o), _dev_ptr(lse),
+                                         _dev_ptr(delta), _dev_ptr(cu_seqlens_kv), cu_seqlens_kv.numel() - 1,
+                                         _dev_ptr(work), n_work, tq, tkv, hq, hkv, D, float(softmax_scale),
+                                         _dev_ptr(q_limit), _dev_ptr(k_from), _dev_ptr(dq_acc), _dev_ptr(dk_acc),
+                                         _dev_ptr(dv_acc), _dev_ptr(scratch), scratch.numel() * scratch.element_size(),
+                                         _stream(stream)))
 
 
 def fcp_grad_finalize(acc, out_bf16, stream=None):

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     pt.mark(0);
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
-    const QTile t = read_record<QTile>(s_rec);
+    const QTile t = read_record<QTile, 12>(s_rec);
     const int head = xcd * heads_here + unit % heads_here;
     const int kvh = head / G;
     uq.prefetch();
@@ -149,13 +149,18 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 
     // Geometry.  Step s < nt0 is key block s of segment 0, step s >= nt0 block s - nt0 of segment 1; inside a segment
     // the key positions grow with the step.  A query group takes part in the leading blocks of a segment (those whose
-    // first key is not after the group's last row) and needs no mask in the leading blocks that all its rows see in
+    // first key the group's last row still sees) and needs no mask in the leading blocks that all its rows see in
     // full; both counts are found once per unit, so that a step costs a few compares instead of its positions.
     struct Span { int a0, b1, u0, u1; };     // active: s < a0 or nt0 <= s < b1; unmasked: s < u0 or nt0 <= s < u1
     auto group_span = [&](int grp) {
       Span sp = {0, 0, 0, 0};
       if (32 * grp >= rows_here) return sp;
-      const int first = t.q_pos0 + 32 * grp, last = t.q_pos0 + min(32 * grp + 31, rows_here - 1);
+      // last key position seen by the group's first and by its last row (the limits grow with the row)
+      int first = t.q_pos0 + 32 * grp, last = t.q_pos0 + min(32 * grp + 31, rows_here - 1);
+      if (p.q_limit) {
+        first = p.q_limit[t.q_row0 + 32 * grp];
+        last = p.q_limit[t.q_row0 + min(32 * grp + 31, rows_here - 1)];
+      }
       auto count = [&](int kpos, int vis, int nt, int& act, int& unm) {
         act = last >= kpos ? min(nt, ((last - kpos) >> 5) + 1) : 0;                 // blocks with kpos + 32 kt <= last
         const int full = first - kpos - 31 >= 0 ? ((first - kpos - 31) >> 5) + 1 : 0;   // ... with kpos + 32 kt + 31 <= first
@@ -193,6 +198,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       }
       // -LSE log2 e (P wave) or -delta (dS wave) of the lane's row
       const float stat = p.stats[(int64_t)role * p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
+      int q_lim = t.q_pos0 + my_row;                 // last key position the lane's row sees
+      if (p.q_limit) q_lim = p.q_limit[t.q_row0 + row_ld];
       // These loads must have arrived before the step loop: the compiler, which does not see the fills, would
       // otherwise wait for them inside the loop with vmcnt(0), and that wait also covers every fill in flight.
       __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -214,7 +221,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         }
       };
       if (role == 0) {
-        const int q_pos = t.q_pos0 + my_row;
         pt.mark(1);
         for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
           wait_fills();
@@ -232,7 +238,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
             const int kt = it - (seg1 ? nt0 : 0);
             const int k_pos0 = (seg1 ? kpos1 : kpos0) + kt * C::BK;
             const int n_valid = min(C::BK, (seg1 ? vis1 : vis0) - kt * C::BK);
-            int hi = min(n_valid, q_pos - k_pos0 + 1) - 4 * g2;     // keys (minus 4 g2) below this bound are seen
+            int hi = min(n_valid, q_lim - k_pos0 + 1) - 4 * g2;     // keys (minus 4 g2) below this bound are seen
             asm volatile("; masked variant" : "+v"(hi));
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -409,11 +415,12 @@ int set_lds_once(K kernel, int bytes, bool* done) {
 
 using fcp::fail;
 
-extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
-                                 const float* delta, const int32_t* cu_seqlens_kv, int32_t n_seqs,
-                                 const fcp_work_desc* work, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq,
-                                 int32_t hkv, int32_t head_dim, float softmax_scale, float* dq_acc, float* dk_acc,
-                                 float* dv_acc, void* scratch, size_t scratch_bytes, void* stream) {
+// Both entry points; q_limit == k_from == NULL is the causal mask.
+static int bwd_step(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                    const float* delta, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                    const fcp_work_desc* work, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq,
+                    int32_t hkv, int32_t head_dim, float softmax_scale, const int32_t* q_limit, const int32_t* k_from,
+                    float* dq_acc, float* dk_acc, float* dv_acc, void* scratch, size_t scratch_bytes, void* stream) {
   fcp::clear_error();
   if (!q || !k || !v || !d_o || !lse || !delta || !cu_seqlens_kv || !dq_acc || !dk_acc || !dv_acc || !scratch)
     return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: null pointer");
@@ -442,9 +449,9 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
   float* stats = reinterpret_cast<float*>(static_cast<char*>(region_q) + fcp::sched_region_bytes(n_work, cap_q));
-  int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
+  int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
-  rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
+  rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
   if ((rc = fcp::launch_row_stats(lse, delta, (int64_t)hq * tq, stats, st)) != FCP_OK) return rc;
@@ -452,6 +459,7 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   fcp::BwdParams p;
   p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v; p.d_o = (const uint16_t*)d_o;
   p.lse = lse; p.delta = delta; p.stats = stats;
+  p.q_limit = q_limit; p.k_from = k_from;
   p.dq = dq_acc; p.dk = dk_acc; p.dv = dv_acc;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.scale = softmax_scale; p.scale_log2 = softmax_scale * fcp::kLog2e;
@@ -485,4 +493,27 @@ extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, co
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
+}
+
+extern "C" int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                                 const float* delta, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                                 const fcp_work_desc* work, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq,
+                                 int32_t hkv, int32_t head_dim, float softmax_scale, float* dq_acc, float* dk_acc,
+                                 float* dv_acc, void* scratch, size_t scratch_bytes, void* stream) {
+  return bwd_step(q, k, v, d_o, lse, delta, cu_seqlens_kv, n_seqs, work, n_work, tq, tkv, hq, hkv, head_dim,
+                  softmax_scale, nullptr, nullptr, dq_acc, dk_acc, dv_acc, scratch, scratch_bytes, stream);
+}
+
+extern "C" int fcp_attn_bwd_step_mixed(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                                       const float* delta, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                                       const fcp_work_desc* work, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq,
+                                       int32_t hkv, int32_t head_dim, float softmax_scale, const int32_t* q_limit,
+                                       const int32_t* k_from, float* dq_acc, float* dk_acc, float* dv_acc,
+                                       void* scratch, size_t scratch_bytes, void* stream) {
+  if (!q_limit || !k_from) {
+    fcp::clear_error();
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step_mixed: q_limit or k_from is NULL");
+  }
+  return bwd_step(q, k, v, d_o, lse, delta, cu_seqlens_kv, n_seqs, work, n_work, tq, tkv, hq, hkv, head_dim,
+                  softmax_scale, q_limit, k_from, dq_acc, dk_acc, dv_acc, scratch, scratch_bytes, stream);
 }

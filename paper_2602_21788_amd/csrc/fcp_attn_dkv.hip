@@ -109,7 +109,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
-    const KTile t = read_record<KTile>(s_rec);
+    const KTile t = read_record<KTile, 15>(s_rec);
     const int kvh = xcd * kvh_here + unit % kvh_here;
     uq.prefetch();
 
@@ -120,8 +120,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     const bool my_key_valid = my_key < n_keys;
     const int64_t kv_row0 = t.kv_row0;
 
-    // query blocks that see the tile: from the block holding the first row at or after the tile's first key
-    const int first_row = max(0, t.k_pos0 - t.q_seq_start);
+    // query blocks that see the tile: from the block holding the first row that sees the tile's first key
+    const int first_row = max(0, t.from_first[0] - t.q_seq_start);
     const int qb0 = first_row / C::BM;
     const int nqb = (t.q_len + C::BM - 1) / C::BM - qb0;       // query blocks per head, >= 1
     const int n_iter = nqb * G;
@@ -178,14 +178,15 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     // row, which holds from a first block on (first_active); its probabilities need the causal mask before a
     // first block (first_unmasked) and always if the tile ends inside the group.  Both are found once per unit, so
     // that a step costs one compare instead of the positions of its rows.
+    auto pick = [](const int32_t (&a)[4], int grp) { return grp == 0 ? a[0] : grp == 1 ? a[1] : grp == 2 ? a[2] : a[3]; };
     auto first_active = [&](int grp) {
-      const int thr = t.k_pos0 + 32 * grp - t.q_seq_start;      // first row of the sequence part that sees the group
+      const int thr = pick(t.from_first, grp) - t.q_seq_start;  // first row of the sequence part that sees the group
       if (32 * grp >= n_keys || thr > t.q_len - 1) return nqb;  // never
       return max(0, (max(thr, 0) >> 5) - qb0);
     };
     auto first_unmasked = [&](int grp) {
       if (32 * grp + 32 > n_keys) return nqb;                   // always masked
-      const int thr = t.k_pos0 + 32 * grp + 31 - t.q_seq_start; // first row that sees all of the group's keys
+      const int thr = pick(t.from_last, grp) - t.q_seq_start;   // first row that sees all of the group's keys
       return max(0, ((max(thr, 0) + 31) >> 5) - qb0);
     };
     int j = 0;
@@ -200,7 +201,9 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
       // own-key fragments, B operand (lane = key column): K for the P wave, V for the dS wave
       bf16x8 kvf[C::NS];
+      int my_key_from = t.k_pos0 + my_key;            // position of the first query that sees the lane's key
       {
+        if (p.k_from) my_key_from = p.k_from[kv_row0 + my_key_ld];
         const uint16_t* src = role == 0 ? p.k : p.v;
         const int64_t off = ((kv_row0 + my_key_ld) * p.hkv + kvh) * D + 8 * g2;
 #pragma unroll
@@ -252,9 +255,9 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           const bool need_mask = jb < j_unmasked;
           f32x4 pr[4];
           if (need_mask) {
-            // register i is block row 8 (i/4) + 4 g2 + i%4; it sees the lane's key if that row >= key position - q_pos0
+            // register i is block row 8 (i/4) + 4 g2 + i%4; it sees the lane's key from the row at position my_key_from on
             const int q_pos0 = t.q_seq_start + (qb0 + jb) * C::BM;
-            int lo = (my_key_valid ? t.k_pos0 + my_key - q_pos0 : 1 << 20) - 4 * g2;
+            int lo = (my_key_valid ? my_key_from - q_pos0 : 1 << 20) - 4 * g2;
             asm volatile("; masked variant" : "+v"(lo));
 #pragma unroll
             for (int i = 0; i < 16; ++i) {

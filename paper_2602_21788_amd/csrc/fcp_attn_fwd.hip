@@ -44,6 +44,7 @@ struct FwdParams {
   const Tile* tiles;
   float* o_part;
   float* lse_part;
+  const int32_t* q_limit;   // [tq] last key position each local query row sees, NULL = its own position (causal)
   int32_t tq, hq, hkv;
   int32_t head_pair;  // 1: a unit is a 128-row tile for TWO heads of one KV head; 0: a 256-row tile for one head
   float scale_log2;   // softmax_scale * log2(e)
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
-    const QTile t = read_record<QTile>(s_rec);
+    const QTile t = read_record<QTile, 12>(s_rec);
     const int head = xcd * heads_here + (unit % units_per_tile) * hpu + (p.head_pair ? grp : 0);
     const int kvh = head / G;
     uq.prefetch();   // next unit's record and the following unit's number start their trips now
@@ -139,9 +140,18 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     const int my_row = wave_r0 + l32;
     const bool row_valid = my_row < t.rows;
     const int row_ld = min(my_row, t.rows - 1);
-    const int q_pos = t.q_pos0 + my_row;
-    const int wave_first_pos = t.q_pos0 + wave_r0;
-    const int wave_last_pos = t.q_pos0 + min(wave_r0 + 31, t.rows - 1);
+    // Last key position the lane's row sees, and the least and greatest such limit among the wave's rows (the limits
+    // grow with the row): the rows' own positions under the causal mask, else the caller's table.
+    int q_lim = t.q_pos0 + my_row;
+    int wave_first_lim = t.q_pos0 + wave_r0;
+    int wave_last_lim = t.q_pos0 + min(wave_r0 + 31, t.rows - 1);
+    if (p.q_limit) {
+      const int32_t* ql = p.q_limit + t.q_row0;
+      q_lim = ql[row_ld];
+      wave_first_lim = ql[min(wave_r0, t.rows - 1)];
+      wave_last_lim = ql[min(wave_r0 + 31, t.rows - 1)];
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);   // before any fill is in flight: later waits count the fills only
+    }
 
     // Key tiles of the unit: nt0 of segment 0, then nt1 of segment 1 (64 keys each, the last of a segment
     // may be ragged).  A wave computes a prefix of them: the tiles its last row sees.
@@ -149,8 +159,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     const int n_iter = nt0 + nt1;
     int n_w = 0;
     if (wave_active) {
-      const int v0 = max(0, min(t.vis[0], wave_last_pos - t.k_pos0[0] + 1));
-      const int v1 = max(0, min(t.vis[1], wave_last_pos - t.k_pos0[1] + 1));
+      const int v0 = max(0, min(t.vis[0], wave_last_lim - t.k_pos0[0] + 1));
+      const int v1 = max(0, min(t.vis[1], wave_last_lim - t.k_pos0[1] + 1));
       const int w0 = (v0 + C::BN - 1) / C::BN, w1 = (v1 + C::BN - 1) / C::BN;
       n_w = w0 == nt0 ? w0 + w1 : w0;
     }
@@ -287,8 +297,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     auto vector_slot = [&](int it) {
       int k_pos0, n_valid;
       tile_geom(it, k_pos0, n_valid);
-      if ((k_pos0 + C::BN - 1 > wave_first_pos) || (n_valid < C::BN)) {   // wave-uniform: causal / segment-end mask
-        const int lim = min(n_valid, q_pos - k_pos0 + 1) - 4 * g2;        // key index (minus 4 g2) below which the lane sees
+      if ((k_pos0 + C::BN - 1 > wave_first_lim) || (n_valid < C::BN)) {   // wave-uniform: mask edge / segment end
+        const int lim = min(n_valid, q_lim - k_pos0 + 1) - 4 * g2;        // key index (minus 4 g2) below which the lane sees
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -388,11 +398,12 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
 
 using fcp::fail;
 
-extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
-                                 int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
-                                 int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
-                                 float softmax_scale, float* o_part, float* lse_part, void* scratch,
-                                 size_t scratch_bytes, void* stream) {
+// Both entry points; q_limit == NULL is the causal mask.
+static int fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                    int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                    int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                    float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part, void* scratch,
+                    size_t scratch_bytes, void* stream) {
   fcp::clear_error();
   if (!q || !k || !v || !cu_seqlens_kv || !o_part || !lse_part || !scratch)
     return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: null pointer");
@@ -417,7 +428,7 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
   // two heads of one KV head per unit when the heads pair up, else twice the rows for one head
   const int head_pair = ((hq / hkv) % 2 == 0) ? 1 : 0;
-  int rc = fcp::launch_schedule(false, head_pair ? fcp::kFwdBM / 2 : fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
+  int rc = fcp::launch_schedule(false, head_pair ? fcp::kFwdBM / 2 : fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, q_limit, nullptr, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
                                 lse_part, (int64_t)n_parts * hq * tq, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
@@ -427,6 +438,7 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   p.hdr = (fcp::SchedHeader*)scratch;
   p.tiles = fcp::sched_tiles(scratch, n_work);
   p.o_part = o_part; p.lse_part = lse_part;
+  p.q_limit = q_limit;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.head_pair = head_pair;
   p.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -456,4 +468,23 @@ extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, co
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
+}
+
+extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                                 int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                                 int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                                 float softmax_scale, float* o_part, float* lse_part, void* scratch,
+                                 size_t scratch_bytes, void* stream) {
+  return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, n_parts, tq, tkv, hq, hkv, head_dim, softmax_scale,
+                  nullptr, o_part, lse_part, scratch, scratch_bytes, stream);
+}
+
+extern "C" int fcp_attn_fwd_step_mixed(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                                       int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                                       int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                                       float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part,
+                                       void* scratch, size_t scratch_bytes, void* stream) {
+  if (!q_limit) { fcp::clear_error(); return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step_mixed: q_limit is NULL"); }
+  return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, n_parts, tq, tkv, hq, hkv, head_dim, softmax_scale,
+                  q_limit, o_part, lse_part, scratch, scratch_bytes, stream);
 }

@@ -11,6 +11,8 @@ struct BwdParams {
   const uint16_t* d_o;
   const float* lse;
   const float* delta;
+  const int32_t* q_limit;    // [tq] last key position each local query row sees, NULL = its own position (causal)
+  const int32_t* k_from;     // [tkv] first query position that sees each pool key, NULL = its own position
   const float* stats;        // two planes [hq][tq]: -LSE * log2 e (-inf for a row without keys), then -delta
   SchedHeader* hdr;          // schedule region of the kernel being launched
   const Tile* tiles;

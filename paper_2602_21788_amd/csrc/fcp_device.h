@@ -231,15 +231,16 @@ struct UnitQueue {
   }
 };
 
-template <typename T>
+// The first NW words of the unit's record (the rest of T reads as zero), as wave-uniform values.
+template <typename T, int NW>
 __device__ inline T read_record(const int32_t* s_rec) {
-  static_assert(sizeof(T) == 64, "16-word record");
+  static_assert(sizeof(T) == 64 && NW <= 16, "16-word record");
   T t;
   int32_t* tw = reinterpret_cast<int32_t*>(&t);
 #pragma unroll
-  for (int i = 0; i < 12; ++i) tw[i] = __builtin_amdgcn_readfirstlane(s_rec[i]);
+  for (int i = 0; i < NW; ++i) tw[i] = __builtin_amdgcn_readfirstlane(s_rec[i]);
 #pragma unroll
-  for (int i = 12; i < 16; ++i) tw[i] = 0;
+  for (int i = NW; i < 16; ++i) tw[i] = 0;
   return t;
 }
 

@@ -51,7 +51,11 @@ struct KTile {                   // a block of keys of one segment of one work i
   int32_t n_keys;                // keys in the block that some row of the item sees
   int32_t q_local_off, q_seq_start, q_len;   // the item's query rows
   int32_t flags;                 // kFlagSeg0Exclusive set iff no other item touches these keys
-  int32_t pad[9];
+  // Per group of 32 keys: the sequence position of the first query that sees the group's first key and of the
+  // first query that sees its last key (of the tile's n_keys), both capped at the item's last row.  With the
+  // causal mask these are the two keys' own positions; with full-attention spans the start of the key's span.
+  int32_t from_first[4], from_last[4];
+  int32_t pad;
 };
 static_assert(sizeof(QTile) == 64 && sizeof(KTile) == 64, "tile records are 16 words");
 struct Tile { int32_t w[16]; };  // storage type of the list
@@ -93,11 +97,16 @@ inline const Tile* sched_tiles(const void* region, int64_t n_work) {
                                        sched_item_off_bytes(n_work) + sched_flags_bytes(n_work));
 }
 
+static_assert(kBwdBN == 4 * 32, "KTile keeps four key groups");
+
 // Builds one tile list in `region` (tiles of `tile` keys if `key_tiles`, else of `tile` query rows;
 // `inner` is the block size of the other dimension used for the cost; kv_row_bytes = hkv*D*2 bounds
 // the segment length so that byte offsets inside a segment fit 31 bits) and, when
 // lse_fill is given, fills it with -inf.
+// q_limit [tq] / k_from [tkv] (device, or NULL for the causal mask): last key position a local query row
+// sees / first query position that sees a pool key.
 int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, int64_t kv_row_bytes,
+                    const int32_t* q_limit, const int32_t* k_from,
                     const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,

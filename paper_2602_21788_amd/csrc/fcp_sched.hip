@@ -46,33 +46,47 @@ __device__ inline bool item_valid(const fcp_work_desc& w, const int32_t* cu, int
   return true;
 }
 
-// keys of segment s that at least one row of [row0, row1) of the item can see
-__device__ inline int32_t visible_len(const fcp_work_desc& w, int s, int32_t last_row) {
-  const int64_t last_q_pos = (int64_t)w.q_seq_start + last_row;
-  int64_t v = last_q_pos - w.k_seq_start[s] + 1;
+// The mask in the form every kernel uses: row i sees the keys at positions 0 .. limit(i), a key is seen by the
+// rows from position from(key) on; both grow with the position.  Causal: limit = the row's own position,
+// from = the key's own position; with full-attention spans the tables the caller passed.
+struct MaskTables {
+  const int32_t* q_limit;   // [tq] by local query row, or NULL
+  const int32_t* k_from;    // [tkv] by pool row, or NULL
+  __device__ int64_t limit(const fcp_work_desc& w, int32_t row) const {
+    return q_limit ? (int64_t)q_limit[w.q_local_off + row] : (int64_t)w.q_seq_start + row;
+  }
+  __device__ int64_t from(const fcp_work_desc& w, const int32_t* cu, int64_t k_pos) const {
+    return k_from ? (int64_t)k_from[cu[w.seq] + k_pos] : k_pos;
+  }
+};
+
+// keys of segment s that row `last_row` of the item (hence any row up to it) can see
+__device__ inline int32_t visible_len(const MaskTables& m, const fcp_work_desc& w, int s, int32_t last_row) {
+  int64_t v = m.limit(w, last_row) - w.k_seq_start[s] + 1;
   if (v < 0) v = 0;
   if (v > w.k_len[s]) v = w.k_len[s];
   return (int32_t)v;
 }
 
 // query tile qt (of `tile` rows): cost = key blocks (of `inner` keys) its last row sees
-__device__ inline int32_t fwd_cost(const fcp_work_desc& w, int32_t qt, int32_t tile, int32_t inner) {
+__device__ inline int32_t fwd_cost(const MaskTables& m, const fcp_work_desc& w, int32_t qt, int32_t tile, int32_t inner) {
   int32_t last_row = min((qt + 1) * tile, w.q_len) - 1;
   int32_t c = 0;
-  for (int s = 0; s < w.n_seg; ++s) c += ceil_div(visible_len(w, s, last_row), inner);
+  for (int s = 0; s < w.n_seg; ++s) c += ceil_div(visible_len(m, w, s, last_row), inner);
   return c;
 }
 
 // key tile kt (of `tile` keys) of segment s: cost = query blocks (of `inner` rows) that see its first key
-__device__ inline int32_t bwd_cost(const fcp_work_desc& w, int s, int32_t kt, int32_t tile, int32_t inner) {
+__device__ inline int32_t bwd_cost(const MaskTables& m, const int32_t* cu, const fcp_work_desc& w, int s, int32_t kt,
+                                   int32_t tile, int32_t inner) {
   const int64_t first_k_pos = (int64_t)w.k_seq_start[s] + (int64_t)kt * tile;
-  int64_t first_row = first_k_pos - w.q_seq_start;
+  int64_t first_row = m.from(w, cu, first_k_pos) - w.q_seq_start;
   if (first_row < 0) first_row = 0;
   const int64_t rows = (int64_t)w.q_len - first_row;
   return rows <= 0 ? 0 : (int32_t)((rows + inner - 1) / inner);
 }
 
-__device__ inline ItemInfo item_info(const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
+__device__ inline ItemInfo item_info(const MaskTables& m, const fcp_work_desc& w, const int32_t* cu, int32_t n_seqs,
                                      int32_t tq, int32_t tkv, int32_t n_parts, bool backward,
                                      bool check_step, int32_t tile, int32_t inner, int32_t max_seg_keys) {
   ItemInfo r{false, 0, 0, 0};
@@ -80,10 +94,10 @@ __device__ inline ItemInfo item_info(const fcp_work_desc& w, const int32_t* cu, 
   if (!r.ok) return r;
   if (!backward) {
     r.n_tiles = ceil_div(w.q_len, tile);
-    r.max_cost = fwd_cost(w, r.n_tiles - 1, tile, inner);
+    r.max_cost = fwd_cost(m, w, r.n_tiles - 1, tile, inner);
   } else {
-    r.nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), tile);
-    int32_t nt1 = w.n_seg > 1 ? ceil_div(visible_len(w, 1, w.q_len - 1), tile) : 0;
+    r.nt0 = ceil_div(visible_len(m, w, 0, w.q_len - 1), tile);
+    int32_t nt1 = w.n_seg > 1 ? ceil_div(visible_len(m, w, 1, w.q_len - 1), tile) : 0;
     r.n_tiles = r.nt0 + nt1;
     r.max_cost = ceil_div(w.q_len, inner);
   }
@@ -113,7 +127,7 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32
 }
 
 __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
-    int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys,
+    int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
     const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
     int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
@@ -139,7 +153,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     int32_t cnt = 0;
     if (i < n_work) {
       const fcp_work_desc w = work[i];
-      const ItemInfo info = item_info(w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0, tile, inner, max_seg_keys);
+      const ItemInfo info = item_info(m, w, cu, n_seqs, tq, tkv, n_parts, backward != 0, check_step != 0, tile, inner, max_seg_keys);
       if (!info.ok) atomicAdd(&s_rej, 1);
       cnt = info.n_tiles;
       if (info.max_cost > 0) atomicMax(&s_max, info.max_cost);
@@ -224,23 +238,29 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
       for (int sg = 0; sg < 2; ++sg) {
         q->kv_row0[sg] = sg < w.n_seg ? row0_kv + w.k_seq_start[sg] : 0;
         q->k_pos0[sg] = sg < w.n_seg ? w.k_seq_start[sg] : 0;
-        q->vis[sg] = sg < w.n_seg ? visible_len(w, sg, r0 + q->rows - 1) : 0;
+        q->vis[sg] = sg < w.n_seg ? visible_len(m, w, sg, r0 + q->rows - 1) : 0;
       }
       q->flags = fl;
-      return fwd_cost(w, local, tile, inner);
+      return fwd_cost(m, w, local, tile, inner);
     }
-    const int32_t nt0 = ceil_div(visible_len(w, 0, w.q_len - 1), tile);
+    const int32_t nt0 = ceil_div(visible_len(m, w, 0, w.q_len - 1), tile);
     const int sg = local >= nt0 ? 1 : 0;
     const int32_t kt = local - (sg ? nt0 : 0);
     KTile* k = reinterpret_cast<KTile*>(&out);
     k->kv_row0 = row0_kv + w.k_seq_start[sg] + kt * tile;
     k->k_pos0 = w.k_seq_start[sg] + kt * tile;
-    k->n_keys = min(tile, visible_len(w, sg, w.q_len - 1) - kt * tile);
+    k->n_keys = min(tile, visible_len(m, w, sg, w.q_len - 1) - kt * tile);
+    const int64_t last_q_pos = (int64_t)w.q_seq_start + w.q_len - 1;
+    for (int g = 0; g < 4; ++g) {
+      const int32_t first_key = min(32 * g, k->n_keys - 1), last_key = min(32 * g + 31, k->n_keys - 1);
+      k->from_first[g] = (int32_t)min(last_q_pos, m.from(w, cu, (int64_t)k->k_pos0 + first_key));
+      k->from_last[g] = (int32_t)min(last_q_pos, m.from(w, cu, (int64_t)k->k_pos0 + last_key));
+    }
     k->q_local_off = w.q_local_off;
     k->q_seq_start = w.q_seq_start;
     k->q_len = w.q_len;
     k->flags = (fl & (sg ? kFlagSeg1Exclusive : kFlagSeg0Exclusive)) ? kFlagSeg0Exclusive : 0;
-    return bwd_cost(w, sg, kt, tile, inner);
+    return bwd_cost(m, cu, w, sg, kt, tile, inner);
   };
 
   for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
@@ -290,6 +310,7 @@ int64_t kv_tile_cap(int32_t tkv, int64_t n_work) {
 }
 
 int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_bytes,
+                    const int32_t* q_limit, const int32_t* k_from,
                     const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
@@ -307,7 +328,7 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
   }
   hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks), dim3(kSchedThreads), 0, stream,
                      backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner,
-                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
+                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
                      (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;

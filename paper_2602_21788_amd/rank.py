@@ -29,12 +29,17 @@ class RankAttention:
     """Buffers and launches for one rank of a planned batch."""
 
     def __init__(self, seq_lens, cp_degree, rank, hq, hkv, head_dim, softmax_scale=None,
-                 base_rank=None, device="cuda:0"):
+                 base_rank=None, device="cuda:0", spans=None):
+        """spans: optional full-attention spans [(seq, start, len), ...] (mixed mask); None = causal."""
         self.device = torch.device(device)
         self.hq, self.hkv, self.D = hq, hkv, head_dim
         self.scale = float(softmax_scale) if softmax_scale is not None else 1.0 / float(np.sqrt(head_dim))
         self.seq_lens = np.asarray(seq_lens, np.int32)
-        self.chunks, self.work_all = B.fcp_shard_plan(seq_lens, cp_degree, base_rank)
+        self.spans = spans
+        if spans is None:
+            self.chunks, self.work_all = B.fcp_shard_plan(seq_lens, cp_degree, base_rank)
+        else:
+            self.chunks, self.work_all = B.fcp_shard_plan_mixed(seq_lens, cp_degree, spans, base_rank)
         self.rank = rank
         self.my_chunks = self.chunks[self.chunks["rank"] == rank]
         self.work = np.ascontiguousarray(self.work_all[self.work_all["rank"] == rank])
@@ -52,6 +57,11 @@ class RankAttention:
         self.work_d = torch.from_numpy(self.work.view(np.uint8).copy()).to(dev) if len(self.work) else \
             torch.zeros(B.WORK_DTYPE.itemsize, dtype=torch.uint8, device=dev)[:0]
         self.n_work = len(self.work)
+        self.q_limit_d = self.k_from_d = None
+        if spans is not None:
+            self.q_limit, self.k_from, self.eta = B.fcp_mask_tables(self.seq_lens, spans, self.chunks, rank)
+            self.q_limit_d = torch.from_numpy(self.q_limit).to(dev)
+            self.k_from_d = torch.from_numpy(self.k_from).to(dev)
         nb_f = B.fcp_scratch_bytes(B.FCP_SCRATCH_FWD, self.tq, self.tkv, hq, hkv, head_dim, self.n_work, self.n_parts)
         nb_b = B.fcp_scratch_bytes(B.FCP_SCRATCH_BWD, self.tq, self.tkv, hq, hkv, head_dim, self.n_work, self.n_parts)
         self.scratch_f = torch.empty(nb_f, dtype=torch.uint8, device=dev)
@@ -91,6 +101,10 @@ class RankAttention:
 
     # -- passes -----------------------------------------------------------------------
     def forward_steps(self, stream=None):
+        if self.spans is not None:
+            B.fcp_attn_fwd_step_mixed(self.q, self.k, self.v, self.cu_d, self.work_d, self.n_parts, self.scale,
+                                      self.q_limit_d, self.o_part, self.lse_part, self.scratch_f, stream)
+            return
         B.fcp_attn_fwd_step(self.q, self.k, self.v, self.cu_d, self.work_d, self.n_parts, self.scale,
                             self.o_part, self.lse_part, self.scratch_f, stream)
 
@@ -108,6 +122,11 @@ class RankAttention:
         B.fcp_attn_bwd_delta(self.o, self.d_o, self.delta, stream)
 
     def backward_steps(self, stream=None):
+        if self.spans is not None:
+            B.fcp_attn_bwd_step_mixed(self.q, self.k, self.v, self.d_o, self.lse, self.delta, self.cu_d, self.work_d,
+                                      self.scale, self.q_limit_d, self.k_from_d, self.dq_acc, self.dk_acc, self.dv_acc,
+                                      self.scratch_b, stream)
+            return
         B.fcp_attn_bwd_step(self.q, self.k, self.v, self.d_o, self.lse, self.delta, self.cu_d, self.work_d,
                             self.scale, self.dq_acc, self.dk_acc, self.dv_acc, self.scratch_b, stream)
 
@@ -124,7 +143,10 @@ class RankAttention:
 
     # -- bookkeeping ------------------------------------------------------------------
     def pairs(self) -> int:
-        """Visible (query, key) pairs of this rank: sum over its rows of (position + 1)."""
+        """Visible (query, key) pairs of this rank: sum over its rows of (position + 1), or of
+        (last visible key position + 1) under a mixed mask."""
+        if self.spans is not None:
+            return int(self.q_limit.astype(np.int64).sum()) + self.tq
         tot = 0
         for c in self.my_chunks:
             a, n = int(c["seq_start"]), int(c["len"])

@@ -26,12 +26,14 @@ def bf16_tensor_to_f64(t):
     return synth.bf16_bits_to_f64(t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
 
 
-def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label=""):
-    """Full element-by-element comparison of one rank (small workloads)."""
+def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label="", spans=None):
+    """Full element-by-element comparison of one rank (small workloads).  spans: full-attention spans
+    [(seq, start, len), ...] of a mixed mask, None = causal."""
     import torch
     from paper_2602_21788_amd.rank import RankAttention
-    ra = RankAttention(wl.seq_lens, wl.cp_degree, rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
-    ochunks, owork = oplan.shard_plan(wl.seq_lens, wl.cp_degree)
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
+    ochunks, owork = oplan.shard_plan(wl.seq_lens, wl.cp_degree, spans=spans)
+    sid = None if spans is None else oplan.span_ids(wl.seq_lens, spans)
     assert ra.chunks.tobytes() == ochunks.tobytes() and ra.work_all.tobytes() == owork.tobytes()
     rows = oplan.rank_rows(ochunks, wl.cu_seqlens, rank)
     if len(rows) == 0:
@@ -41,7 +43,7 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
     torch.cuda.synchronize()
     n_tiles, n_rej = __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_f)
     assert n_rej == 0, f"{label}: {n_rej} work items rejected"
-    O_ref, LSE_ref = oattn.attn_fwd(q, k, v, wl.cu_seqlens, wl.softmax_scale, rows)
+    O_ref, LSE_ref = oattn.attn_fwd(q, k, v, wl.cu_seqlens, wl.softmax_scale, rows, span_id=sid)
     O = bf16_tensor_to_f64(ra.o)
     LSE = ra.lse.cpu().numpy().astype(np.float64).T          # [tq, hq]
     res = {"O": rel_err(O, O_ref), "LSE": float(np.abs(LSE - LSE_ref).max())}
@@ -50,7 +52,7 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
     assert res["LSE"] <= TOL_LSE_ABS, (label, res)
     if check_partials:
         qf, kf, vf = (synth.bf16_bits_to_f64(x) for x in (q, k, v))
-        Op_ref, Lp_ref = oplan.rank_partials(qf, kf, vf, wl.cu_seqlens, ochunks, owork, rank, wl.softmax_scale)
+        Op_ref, Lp_ref = oplan.rank_partials(qf, kf, vf, wl.cu_seqlens, ochunks, owork, rank, wl.softmax_scale, span_id=sid)
         Op = ra.o_part.cpu().numpy().astype(np.float64)
         Lp = ra.lse_part.cpu().numpy().astype(np.float64).transpose(0, 2, 1)
         assert Op.shape == Op_ref.shape
@@ -65,8 +67,8 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
         torch.cuda.synchronize()
         n_tiles, n_rej = __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_b)
         assert n_rej == 0, f"{label}: {n_rej} work items rejected (bwd)"
-        dQ_ref = oattn.attn_dq(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref)
-        dK_ref, dV_ref = oattn.attn_dkv(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref)
+        dQ_ref = oattn.attn_dq(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref, span_id=sid)
+        dK_ref, dV_ref = oattn.attn_dkv(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref, span_id=sid)
         got = {"dQ": bf16_tensor_to_f64(ra.dq), "dK": bf16_tensor_to_f64(ra.dk), "dV": bf16_tensor_to_f64(ra.dv)}
         for name, ref in (("dQ", dQ_ref), ("dK", dK_ref), ("dV", dV_ref)):
             assert np.isfinite(got[name]).all(), (label, name)
