@@ -6,7 +6,8 @@ A "step" is one pass of the whole path for the reported rank of the workload:
   fcp_attn_bwd_step (all ring steps) -> fcp_grad_finalize x3,
 with every input already resident in HBM.  The metric is causal-effective TFLOP/s:
 14 * pairs * head_dim * hq / time (4 forward + 10 backward flops per visible pair, channel
-and head; masked pairs are not counted).
+and head; masked pairs are not counted).  --mask mixed times the same path through the
+*_mixed entry points on the workload with synthetic image spans (not the headline number).
 
 Prints ONE JSON line (see the keys below); `roofline` is for the dominant kernel (the
 backward step), `cpu_baseline` times the fp64 CPU oracle on a bounded sample of the same
@@ -30,11 +31,13 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_BWD_TRAFFIC_BYTES = {"packed32k_lognormal24_h32x8_D128": 5.62e9}
 
 
-def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30):
+def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30, spans=None):
     """Times the oracle (as it stands) on a bounded sample: one KV-head group (hq/hkv query
     heads + 1 KV head) and every `stride`-th of the rank's rows; forward, dQ and the dK/dV
     partial of those rows.  Heads and rows are independent, so the rate carries over."""
     from oracle import attn as oattn
+    from oracle import plan as oplan
+    sid = None if spans is None else oplan.span_ids(wl.seq_lens, spans)
     G = wl.hq // wl.hkv
     stride = max(1, len(rows) // budget_rows)
     sample = np.ascontiguousarray(rows[::stride])
@@ -43,10 +46,14 @@ def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30):
     cu = wl.cu_seqlens
     seq_of = np.searchsorted(cu, sample, side="right") - 1
     pairs = int((sample - cu[seq_of] + 1).sum())
+    if sid is not None:     # plus the keys after the row inside its own span
+        for n, (sk, st, ln) in enumerate(spans):
+            in_span = sample[sid[sample] == n]
+            pairs += int((cu[sk] + st + ln - 1 - in_span).sum())
     t0 = time.perf_counter()
-    O, LSE = oattn.attn_fwd(qs, ks, vs, cu, wl.softmax_scale, sample)
-    oattn.attn_dq(qs, ks, vs, dos, cu, wl.softmax_scale, sample, O, LSE)
-    oattn.attn_dkv(qs, ks, vs, dos, cu, wl.softmax_scale, sample, O, LSE)
+    O, LSE = oattn.attn_fwd(qs, ks, vs, cu, wl.softmax_scale, sample, span_id=sid)
+    oattn.attn_dq(qs, ks, vs, dos, cu, wl.softmax_scale, sample, O, LSE, span_id=sid)
+    oattn.attn_dkv(qs, ks, vs, dos, cu, wl.softmax_scale, sample, O, LSE, span_id=sid)
     dt = time.perf_counter() - t0
     flops = 14.0 * pairs * wl.head_dim * G
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": oattn.num_threads(), "kind": "oracle",
@@ -60,6 +67,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, help="index into the five workloads (default: 32K packed)")
+    ap.add_argument("--mask", choices=["causal", "mixed"], default="causal",
+                    help="mixed: the same workload with synthetic image spans (576 tokens each, about 35 %% of a "
+                         "sequence) that attend in full; pairs and flops then count the pairs visible under that mask")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy after the timed steps: the reference dispatch for scaling "
@@ -80,8 +90,10 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.make_workload(args.workload)
     q, k, v, do = synth.draw_qkvdo(wl)
-    ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
+    spans = synth.image_spans(wl.seq_lens, wl.seed) if args.mask == "mixed" else None
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
     ra.set_inputs(q, k, v, do)
+    wl_name = wl.name + ("_img576" if spans is not None else "")
     pairs = ra.pairs()
     flops_fwd = 4.0 * pairs * wl.head_dim * wl.hq
     flops_bwd = 10.0 * pairs * wl.head_dim * wl.hq
@@ -126,13 +138,13 @@ def main():
         "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
+        "config": {"workload": wl_name, "mask": args.mask, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
                    "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
                    "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
                    "seed": wl.seed},
         "roofline": {"bound": "mfma", "kernel": f"fcp_attn_bwd_step (dkv_kernel<{wl.head_dim}> + dq_kernel<{wl.head_dim}>)",
                      "achieved": bwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(wl.name)},
+                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(wl_name)},
         "kernels": {
             "fwd_step": {"ms": seg_ms["fwd_step"], "tflops": fwd_tflops, "frac_mfma_peak": fwd_tflops / PEAK_BF16_TFLOPS},
             "bwd_step": {"ms": seg_ms["bwd_step"], "tflops": bwd_tflops, "frac_mfma_peak": bwd_tflops / PEAK_BF16_TFLOPS},
@@ -148,7 +160,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, do, ra.rows)
+        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, do, ra.rows, spans=spans)
     print(json.dumps(out))
 
 

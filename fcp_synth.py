@@ -142,6 +142,23 @@ def make_workload(cfg: int, seed: int = 0) -> Workload:
     return wl
 
 
+def image_spans(seq_lens, seed: int = 0, span_len: int = 576, image_fraction: float = 0.35):
+    """Full-attention spans of a synthetic multimodal batch: every sequence longer than one image gets images of
+    `span_len` tokens (a 24 x 24 patch grid) separated by text runs, until about `image_fraction` of its tokens
+    are image tokens; shorter sequences stay text only.  Returns [(seq, start, len), ...] sorted by (seq, start)."""
+    rng = np.random.default_rng(seed + 77)
+    spans = []
+    for k, L in enumerate(int(x) for x in seq_lens):
+        n_img = int(L * image_fraction) // span_len
+        if n_img == 0:
+            continue
+        text = L - n_img * span_len
+        cuts = np.sort(rng.integers(0, text + 1, size=n_img))     # text tokens before each image
+        for i, c in enumerate(cuts):
+            spans.append((k, int(c) + i * span_len, span_len))
+    return spans
+
+
 def custom_workload(seq_lens, cp_degree, hq, hkv, head_dim, rank=0, seed=0, name="custom") -> Workload:
     wl = Workload(name, np.asarray(seq_lens, np.int32), np.asarray(cp_degree, np.int32),
                   hq, hkv, head_dim, rank=rank, seed=seed)

@@ -108,3 +108,44 @@ def test_empty_span_list_equals_causal_entry_points():
         outs.append([x.clone() for x in (ra.o, ra.lse, ra.dq, ra.dk, ra.dv)])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_cfg2_image_spans_full_size_sampled():
+    """The 32K-token packed workload with its synthetic image spans, in the launch configuration `bench.py --mask
+    mixed` times (rank 0, 32 query / 8 KV heads, D = 128): O, LSE, dQ of every 61st row and dK, dV in full for the
+    query heads of KV head 3 (heads are independent, so a head subset is exact for those heads)."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    from parity import TOL_LSE_ABS, bf16_tensor_to_f64
+    wl = synth.make_workload(2)
+    spans = synth.image_spans(wl.seq_lens, wl.seed)
+    sid = oplan.span_ids(wl.seq_lens, spans)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    _say(f"cfg2 {wl.name} + {len(spans)} image spans, rank {wl.rank}: full-size run, sampled comparison")
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
+    ra.set_inputs(q, k, v, do)
+    ra.forward()
+    ra.backward()
+    torch.cuda.synchronize()
+    ochunks, _ = oplan.shard_plan(wl.seq_lens, wl.cp_degree, spans=spans)
+    rows = oplan.rank_rows(ochunks, wl.cu_seqlens, wl.rank)
+    O = bf16_tensor_to_f64(ra.o)
+    LSE = ra.lse.cpu().numpy().astype(np.float64).T
+    dQ, dK, dV = (bf16_tensor_to_f64(x) for x in (ra.dq, ra.dk, ra.dv))
+    for x in (O, LSE, dQ, dK, dV):
+        assert np.isfinite(x).all()
+    G, kvh = wl.hq // wl.hkv, 3
+    sel = np.arange(0, len(rows), 61)
+    hs = slice(kvh * G, (kvh + 1) * G)
+    qs, dos = np.ascontiguousarray(q[:, hs]), np.ascontiguousarray(do[:, hs])
+    ks, vs = np.ascontiguousarray(k[:, kvh:kvh + 1]), np.ascontiguousarray(v[:, kvh:kvh + 1])
+    O_ref, LSE_ref = oattn.attn_fwd(qs, ks, vs, wl.cu_seqlens, wl.softmax_scale, rows, span_id=sid)
+    dQ_ref = oattn.attn_dq(qs, ks, vs, dos, wl.cu_seqlens, wl.softmax_scale, rows[sel], O_ref[sel], LSE_ref[sel], span_id=sid)
+    dK_ref, dV_ref = oattn.attn_dkv(qs, ks, vs, dos, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref, span_id=sid)
+    e = {"O": rel_err(O[sel, hs], O_ref[sel]), "LSE": float(np.abs(LSE[sel, hs] - LSE_ref[sel]).max()),
+         "dQ": rel_err(dQ[sel, hs], dQ_ref), "dK": rel_err(dK[:, kvh:kvh + 1], dK_ref), "dV": rel_err(dV[:, kvh:kvh + 1], dV_ref)}
+    _say(f"  kv head {kvh}: {e}")
+    assert e["LSE"] <= TOL_LSE_ABS and all(e[n] <= TOL_BF16_REL for n in ("O", "dQ", "dK", "dV"))
+    # the image spans did matter: the causal result of the same inputs differs
+    O_c, _ = oattn.attn_fwd(qs, ks, vs, wl.cu_seqlens, wl.softmax_scale, rows[sel])
+    assert rel_err(O_c, O_ref[sel]) > 0.05
