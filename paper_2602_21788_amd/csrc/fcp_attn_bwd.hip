@@ -401,15 +401,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
   pt.end(p.hdr);
 }
 
-template <typename K>
-int set_lds_once(K kernel, int bytes, bool* done) {
-  if (!*done) {
-    FCP_HIP_CHECK(hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
-    *done = true;
-  }
-  return FCP_OK;
-}
-
 }  // namespace
 }  // namespace fcp
 
@@ -483,12 +474,12 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   p.hdr = (fcp::SchedHeader*)region_q;
   p.tiles = fcp::sched_tiles(region_q, n_work);
   if (head_dim == 128) {
-    static bool done = false;
-    if ((rc = fcp::set_lds_once(fcp::dq_kernel<128>, fcp::DqCfg<128>::LDS_BYTES, &done)) != FCP_OK) return rc;
+    static std::atomic<uint64_t> lds_done;
+    if ((rc = fcp::raise_lds_limit((const void*)fcp::dq_kernel<128>, fcp::DqCfg<128>::LDS_BYTES, lds_done)) != FCP_OK) return rc;
     hipLaunchKernelGGL(fcp::dq_kernel<128>, grid_for(cap_q * hq, 1), dim3(768), fcp::DqCfg<128>::LDS_BYTES, st, p);
   } else {
-    static bool done = false;
-    if ((rc = fcp::set_lds_once(fcp::dq_kernel<64>, fcp::DqCfg<64>::LDS_BYTES, &done)) != FCP_OK) return rc;
+    static std::atomic<uint64_t> lds_done;
+    if ((rc = fcp::raise_lds_limit((const void*)fcp::dq_kernel<64>, fcp::DqCfg<64>::LDS_BYTES, lds_done)) != FCP_OK) return rc;
     hipLaunchKernelGGL(fcp::dq_kernel<64>, grid_for(cap_q * hq, 1), dim3(768), fcp::DqCfg<64>::LDS_BYTES, st, p);
   }
   FCP_HIP_CHECK(hipGetLastError());

@@ -483,18 +483,13 @@ int launch_dkv(const BwdParams& p, int head_dim, int64_t units, int n_cu, hipStr
   int64_t blocks = n_cu;                               // one 1024-thread block per CU
   if (blocks > units) blocks = (units + 7) / 8 * 8;   // a multiple of the XCD count
   if (blocks < 8) blocks = 8;
-  static bool attr_done[2] = {false, false};
+  static std::atomic<uint64_t> lds_done[2];
+  int rc;
   if (head_dim == 128) {
-    if (!attr_done[0]) {
-      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)dkv_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<128>::LDS_BYTES));
-      attr_done[0] = true;
-    }
+    if ((rc = raise_lds_limit((const void*)dkv_kernel<128>, DkvCfg<128>::LDS_BYTES, lds_done[0])) != FCP_OK) return rc;
     hipLaunchKernelGGL(dkv_kernel<128>, dim3((unsigned)blocks), dim3(1024), DkvCfg<128>::LDS_BYTES, stream, p);
   } else {
-    if (!attr_done[1]) {
-      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)dkv_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, DkvCfg<64>::LDS_BYTES));
-      attr_done[1] = true;
-    }
+    if ((rc = raise_lds_limit((const void*)dkv_kernel<64>, DkvCfg<64>::LDS_BYTES, lds_done[1])) != FCP_OK) return rc;
     hipLaunchKernelGGL(dkv_kernel<64>, dim3((unsigned)blocks), dim3(1024), DkvCfg<64>::LDS_BYTES, stream, p);
   }
   FCP_HIP_CHECK(hipGetLastError());

@@ -450,20 +450,12 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   int64_t blocks = n_cu;                               // one 512-thread block per CU
   if (blocks > units) blocks = (units + 7) / 8 * 8;   // keep a multiple of the XCD count
   if (blocks < 8) blocks = 8;
-  static bool attr_done[2] = {false, false};
+  static std::atomic<uint64_t> lds_done[2];
   if (head_dim == 128) {
-    if (!attr_done[0]) {
-      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::fwd_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        fcp::FwdCfg<128>::LDS_BYTES));
-      attr_done[0] = true;
-    }
+    if ((rc = fcp::raise_lds_limit((const void*)fcp::fwd_kernel<128>, fcp::FwdCfg<128>::LDS_BYTES, lds_done[0])) != FCP_OK) return rc;
     hipLaunchKernelGGL(fcp::fwd_kernel<128>, dim3((unsigned)blocks), dim3(512), fcp::FwdCfg<128>::LDS_BYTES, st, p);
   } else {
-    if (!attr_done[1]) {
-      FCP_HIP_CHECK(hipFuncSetAttribute((const void*)fcp::fwd_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        fcp::FwdCfg<64>::LDS_BYTES));
-      attr_done[1] = true;
-    }
+    if ((rc = fcp::raise_lds_limit((const void*)fcp::fwd_kernel<64>, fcp::FwdCfg<64>::LDS_BYTES, lds_done[1])) != FCP_OK) return rc;
     hipLaunchKernelGGL(fcp::fwd_kernel<64>, dim3((unsigned)blocks), dim3(512), fcp::FwdCfg<64>::LDS_BYTES, st, p);
   }
   FCP_HIP_CHECK(hipGetLastError());

@@ -2,6 +2,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <atomic>
 #include "fcp.h"
 
 namespace fcp {
@@ -16,6 +18,18 @@ void clear_error();
     if (e__ != hipSuccess)                                                           \
       return ::fcp::fail(FCP_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e__)); \
   } while (0)
+
+// A kernel that uses more than 64 KB of dynamic LDS needs its limit raised once per device; `done` keeps one bit
+// per device (devices past 63 raise it on every call).  Safe to call from several threads.
+inline int raise_lds_limit(const void* kernel, int bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  FCP_HIP_CHECK(hipGetDevice(&dev));
+  const uint64_t bit = dev >= 0 && dev < 64 ? (uint64_t)1 << dev : 0;
+  if (bit && (done.load(std::memory_order_acquire) & bit)) return FCP_OK;
+  FCP_HIP_CHECK(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  done.fetch_or(bit, std::memory_order_release);
+  return FCP_OK;
+}
 
 // ---- device-side schedule kept at the start of the caller's scratch buffer ----------
 // Both attention kernels are persistent: blocks pull (tile, head) units from counters
