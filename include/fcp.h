@@ -215,6 +215,27 @@ int fcp_attn_bwd_step_mixed(const void* q, const void* k, const void* v, const v
                             float* dq_acc, float* dk_acc, float* dv_acc,
                             void* scratch, size_t scratch_bytes, void* stream);
 
+/*
+ * fcp_attn_fwd_step_running -- one ring step fused with the running merge (no partial results, no
+ * fcp_lse_merge): the alternative to the partial + merge pair, for a caller that runs the ring steps of
+ * Sec. 3.2 one after the other.  (o_run, lse_run) hold the merged attention over the keys of the ring steps so
+ * far; for every row of every work item of the call they are replaced by the merge with this step's keys:
+ *   LSE' = ln(exp(LSE) + sum_j exp(s_j)),  O' = (exp(LSE - LSE') O + sum_j exp(s_j - LSE') V_j).
+ * Inside the kernel the previous result simply is the initial state of the online softmax.
+ *   o_run [tq,hq,D] fp32, lse_run [hq,tq] fp32 device, in/out.  Before the first step the caller sets lse_run
+ *         to -inf and o_run to 0.  Rows that no item of the call covers are left as they are.
+ *   o_out [tq,hq,D] bf16 device or NULL: the covered rows' O' rounded to bf16 as well (pass it in every call, or
+ *         at least in the last call that covers a row: a row's last visit may come before the last ring step)
+ *   q_limit: NULL (causal) or as in fcp_attn_fwd_step_mixed.  The items' `step` fields are ignored.
+ * Two items of one call must not share a row (the steps of a ring never do); one call per ring step, in any
+ * order, on one stream.  scratch as for fcp_attn_fwd_step with n_parts = 1.
+ */
+int fcp_attn_fwd_step_running(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                              int32_t n_seqs, const fcp_work_desc* work, int64_t n_work,
+                              int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                              float softmax_scale, const int32_t* q_limit, float* o_run, float* lse_run,
+                              void* o_out, void* scratch, size_t scratch_bytes, void* stream);
+
 /* Cast n fp32 accumulator values to bf16, round to nearest even.  Device pointers. */
 int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, void* stream);
 
@@ -255,6 +276,18 @@ int fcp_plan_groups(const int32_t* seq_lens, const float* eta, int32_t n_seqs, i
                     int64_t tokens_per_rank, const fcp_cost_model* cm, int32_t* group_of_seq,
                     int32_t* n_groups, int32_t* group_d_min, int32_t* group_degree,
                     int32_t* group_base_rank, double* makespan);
+
+/*
+ * fcp_group_shard_args -- HOST ONLY.  The paper executes an atomic group as ONE CP group (Sec. 4.4): every
+ * sequence packed into a group, short ones included, is split over the group's degree.  Turns the result of
+ * fcp_plan_groups into the per-sequence arguments of fcp_shard_plan:
+ *   cp_degree[k] = group_degree[group_of_seq[k]],  base_rank[k] = group_base_rank[group_of_seq[k]].
+ * (fcp_shard_plan itself takes any per-sequence degrees, e.g. short sequences of a group left at degree 1.)
+ *   group_of_seq [n_seqs], group_degree, group_base_rank [n_groups] host in; cp_degree, base_rank [n_seqs] host out.
+ */
+int fcp_group_shard_args(const int32_t* group_of_seq, int32_t n_seqs, const int32_t* group_degree,
+                         const int32_t* group_base_rank, int32_t n_groups, int32_t* cp_degree,
+                         int32_t* base_rank);
 
 /*
  * Reads back what the last fwd/bwd step that used `scratch` recorded: the number of

@@ -127,3 +127,11 @@ def plan(seq_lens, n_ranks, cap_tokens, cm: CostModel, etas=None):
     for g in range(1, len(degrees)):
         base[g] = base[g - 1] + degrees[g - 1]
     return {"group_of_seq": group_of, "d_min": d_min, "degree": degrees, "base_rank": base, "makespan": makespan}
+
+
+def group_shard_args(plan_result):
+    """Per-sequence (cp_degree, base_rank) when every sequence of an atomic group runs at the group's degree
+    (Sec. 4.4: the group is one CP group)."""
+    deg = [plan_result["degree"][g] for g in plan_result["group_of_seq"]]
+    base = [plan_result["base_rank"][g] for g in plan_result["group_of_seq"]]
+    return deg, base

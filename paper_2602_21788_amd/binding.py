@@ -27,7 +27,7 @@ SPAN_DTYPE = np.dtype([("seq", "<i4"), ("start", "<i4"), ("len", "<i4")])
 
 EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_plan_groups", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
            "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status",
-           "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed"]
+           "fcp_group_shard_args", "fcp_attn_fwd_step_running", "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed"]
 
 
 class FcpError(RuntimeError):
@@ -68,12 +68,16 @@ def lib() -> ctypes.CDLL:
         L.fcp_grad_finalize.argtypes = [P, P, I64, P]
         L.fcp_scratch_status.restype = ctypes.c_int
         L.fcp_scratch_status.argtypes = [P, P, P, P]
+        L.fcp_group_shard_args.restype = ctypes.c_int
+        L.fcp_group_shard_args.argtypes = [P, I32, P, P, I32, P, P]
         L.fcp_shard_plan_mixed.restype = ctypes.c_int
         L.fcp_shard_plan_mixed.argtypes = [P, P, P, I32, P, I32, P, I64, P, P, I64, P]
         L.fcp_mask_tables.restype = ctypes.c_int
         L.fcp_mask_tables.argtypes = [P, I32, P, I32, P, I64, I32, P, I64, P, P, P]
         L.fcp_attn_fwd_step_mixed.restype = ctypes.c_int
         L.fcp_attn_fwd_step_mixed.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, I32, F, P, P, P, P, SZ, P]
+        L.fcp_attn_fwd_step_running.restype = ctypes.c_int
+        L.fcp_attn_fwd_step_running.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, F, P, P, P, P, P, SZ, P]
         L.fcp_attn_bwd_step_mixed.restype = ctypes.c_int
         L.fcp_attn_bwd_step_mixed.argtypes = [P, P, P, P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, F, P, P, P, P, P, P,
                                               SZ, P]
@@ -204,6 +208,18 @@ def fcp_plan_groups(seq_lens, n_ranks, tokens_per_rank, cost_model, eta=None):
             "base_rank": base[:n].copy(), "makespan": mk.value}
 
 
+def fcp_group_shard_args(group_of_seq, group_degree, group_base_rank):
+    """Host only.  (cp_degree, base_rank) per sequence for fcp_shard_plan: every sequence at its group's degree."""
+    go = np.ascontiguousarray(group_of_seq, dtype=np.int32)
+    gd = np.ascontiguousarray(group_degree, dtype=np.int32)
+    gb = np.ascontiguousarray(group_base_rank, dtype=np.int32)
+    if gd.shape != gb.shape or go.ndim != 1 or gd.ndim != 1:
+        raise ValueError("group_degree and group_base_rank must be 1-D and the same length")
+    cd, br = np.zeros(len(go), np.int32), np.zeros(len(go), np.int32)
+    _check(lib().fcp_group_shard_args(_np_ptr(go), len(go), _np_ptr(gd), _np_ptr(gb), len(gd), _np_ptr(cd), _np_ptr(br)))
+    return cd, br
+
+
 def fcp_scratch_bytes(which, tq, tkv, hq, hkv, head_dim, n_work, n_parts) -> int:
     return int(lib().fcp_scratch_bytes(which, tq, tkv, hq, hkv, head_dim, n_work, n_parts))
 
@@ -232,6 +248,20 @@ def fcp_attn_fwd_step_mixed(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale
                                          cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, n_parts, tq, tkv, hq, hkv, D,
                                          float(softmax_scale), _dev_ptr(q_limit), _dev_ptr(o_part), _dev_ptr(lse_part),
                                          _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_attn_fwd_step_running(q, k, v, cu_seqlens_kv, work, softmax_scale, o_run, lse_run, scratch, o_out=None,
+                              q_limit=None, stream=None):
+    """One ring step merged into the running result (o_run [tq,hq,D] fp32, lse_run [hq,tq] fp32, in/out);
+    o_out: optional bf16 [tq,hq,D]; q_limit: optional int32 [tq] (mixed mask)."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_fwd_step_running(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(cu_seqlens_kv),
+                                           cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, tq, tkv, hq, hkv, D,
+                                           float(softmax_scale), _dev_ptr(q_limit), _dev_ptr(o_run), _dev_ptr(lse_run),
+                                           _dev_ptr(o_out), _dev_ptr(scratch), scratch.numel() * scratch.element_size(),
+                                           _stream(stream)))
 
 
 def fcp_lse_merge(o_part, lse_part, o, lse, stream=None):

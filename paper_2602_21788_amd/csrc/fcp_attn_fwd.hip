@@ -45,6 +45,8 @@ struct FwdParams {
   float* o_part;
   float* lse_part;
   const int32_t* q_limit;   // [tq] last key position each local query row sees, NULL = its own position (causal)
+  uint16_t* o_out;          // running mode only: merged O as bf16 [tq,hq,D], or NULL
+  int32_t running;          // 1: slot 0 of o_part / lse_part is the caller's running result, continued and rewritten
   int32_t tq, hq, hkv;
   int32_t head_pair;  // 1: a unit is a 128-row tile for TWO heads of one KV head; 0: a 256-row tile for one head
   float scale_log2;   // softmax_scale * log2(e)
@@ -223,6 +225,30 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     for (int db = 0; db < D / 32; ++db) oacc[db] = zero16();
     float m_run = -INFINITY;   // running maximum in log2 units (score * scale_log2)
     float l_run = 0.f;         // this lane's share of the running sum
+    const int slot = p.running ? 0 : t.step;
+    if (p.running) {
+      // The caller's merged result of the earlier ring steps is one more block of keys already folded into the
+      // state: maximum = its LSE, sum 1 (held by the lower half-wave), accumulator = its normalised O.  A row
+      // without earlier keys (LSE = -inf, O = 0 by contract) starts like any other.
+      const float lse_prev = p.lse_part[(int64_t)head * p.tq + t.q_row0 + row_ld];
+      const int row_bytes = p.hq * D * 4;
+      const int n_wave_rows = t.rows - wave_r0;
+      const __amdgpu_buffer_rsrc_t ri = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(p.o_part + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
+          n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 4 : 0, 0x00020000);
+      const int o_voff = 4 * g2 * row_bytes + 4 * l32;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+          oacc[db][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+              ri, o_voff, (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db, 0));
+      if (lse_prev > -INFINITY) {
+        m_run = lse_prev * kLog2e;
+        l_run = g2 == 0 ? 1.f : 0.f;
+      }
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);   // not inside the tile loop, where a wait would also cover the fills
+    }
     f32x16 sacc[2];            // scores of the current tile: sacc[kb][i] = key 32 kb + 8 (i/4) + 4 g2 + (i%4), query l32
     bf16x8 pf[4];              // P^T of the current tile as B operands: k-step tt covers keys 16 tt .. 16 tt + 15
 
@@ -372,7 +398,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       const int row_bytes = p.hq * D * 4;
       const int n_wave_rows = t.rows - wave_r0;
       const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
-          (void*)(p.o_part + (int64_t)t.step * ((int64_t)p.tq * p.hq * D) + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D),
+          (void*)(p.o_part + (int64_t)slot * ((int64_t)p.tq * p.hq * D) + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D),
           (short)0, n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 4 : 0, 0x00020000);
       const int o_voff = 4 * g2 * row_bytes + 4 * l32;
 #pragma unroll
@@ -384,9 +410,25 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
                                                 (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db, 0);
         }
     }
+    if (p.o_out) {   // running mode: the merged rows as bf16 as well (half a line per store)
+      const int row_bytes = p.hq * D * 2;
+      const int n_wave_rows = t.rows - wave_r0;
+      const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(p.o_out + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
+          n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 2 : 0, 0x00020000);
+      const int o_voff = 4 * g2 * row_bytes + 2 * l32;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const __bf16 val = (__bf16)oacc[db][i];
+          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rb, o_voff,
+                                                (8 * (i / 4) + (i % 4)) * row_bytes + 64 * db, 0);
+        }
+    }
     if (row_valid && g2 == 0) {
       const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-      p.lse_part[(int64_t)t.step * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
+      p.lse_part[(int64_t)slot * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
     }
     uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block (barrier: LDS stages are free)
   }
@@ -403,7 +445,7 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
                     int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
                     int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
                     float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part, void* scratch,
-                    size_t scratch_bytes, void* stream) {
+                    size_t scratch_bytes, void* stream, bool running = false, void* o_out = nullptr) {
   fcp::clear_error();
   if (!q || !k || !v || !cu_seqlens_kv || !o_part || !lse_part || !scratch)
     return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: null pointer");
@@ -429,7 +471,7 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   // two heads of one KV head per unit when the heads pair up, else twice the rows for one head
   const int head_pair = ((hq / hkv) % 2 == 0) ? 1 : 0;
   int rc = fcp::launch_schedule(false, head_pair ? fcp::kFwdBM / 2 : fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, q_limit, nullptr, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
-                                lse_part, (int64_t)n_parts * hq * tq, st);
+                                running ? nullptr : lse_part, (int64_t)n_parts * hq * tq, st);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
 
@@ -439,6 +481,8 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   p.tiles = fcp::sched_tiles(scratch, n_work);
   p.o_part = o_part; p.lse_part = lse_part;
   p.q_limit = q_limit;
+  p.running = running ? 1 : 0;
+  p.o_out = (uint16_t*)o_out;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.head_pair = head_pair;
   p.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -479,4 +523,17 @@ extern "C" int fcp_attn_fwd_step_mixed(const void* q, const void* k, const void*
   if (!q_limit) { fcp::clear_error(); return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step_mixed: q_limit is NULL"); }
   return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, n_parts, tq, tkv, hq, hkv, head_dim, softmax_scale,
                   q_limit, o_part, lse_part, scratch, scratch_bytes, stream);
+}
+
+extern "C" int fcp_attn_fwd_step_running(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                                         int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t tq,
+                                         int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim, float softmax_scale,
+                                         const int32_t* q_limit, float* o_run, float* lse_run, void* o_out,
+                                         void* scratch, size_t scratch_bytes, void* stream) {
+  if (o_out && (reinterpret_cast<uintptr_t>(o_out) & 3u)) {
+    fcp::clear_error();
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step_running: o_out must be 4-byte aligned");
+  }
+  return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, 1, tq, tkv, hq, hkv, head_dim, softmax_scale, q_limit,
+                  o_run, lse_run, scratch, scratch_bytes, stream, true, o_out);
 }

@@ -149,3 +149,27 @@ extern "C" int fcp_plan_groups(const int32_t* seq_lens, const float* eta, int32_
   }
   return FCP_OK;
 }
+
+// The paper's atomic groups run as one CP group (Sec. 4.4): every sequence of a group takes the group's degree
+// and base rank.
+extern "C" int fcp_group_shard_args(const int32_t* group_of_seq, int32_t n_seqs, const int32_t* group_degree,
+                                    const int32_t* group_base_rank, int32_t n_groups, int32_t* cp_degree,
+                                    int32_t* base_rank) {
+  using fcp::fail;
+  fcp::clear_error();
+  if (n_seqs < 0 || n_groups < 0 || (n_seqs > 0 && (!group_of_seq || !cp_degree || !base_rank)) ||
+      (n_groups > 0 && (!group_degree || !group_base_rank)))
+    return fail(FCP_ERR_INVALID_ARG, "fcp_group_shard_args: null argument or negative count");
+  for (int32_t g = 0; g < n_groups; ++g)
+    if (group_degree[g] < 1 || group_base_rank[g] < 0)
+      return fail(FCP_ERR_INVALID_ARG, "fcp_group_shard_args: group %d has degree %d, base rank %d", g, group_degree[g],
+                  group_base_rank[g]);
+  for (int32_t k = 0; k < n_seqs; ++k) {
+    const int32_t g = group_of_seq[k];
+    if (g < 0 || g >= n_groups)
+      return fail(FCP_ERR_INVALID_ARG, "fcp_group_shard_args: group_of_seq[%d] = %d out of range", k, g);
+    cp_degree[k] = group_degree[g];
+    base_rank[k] = group_base_rank[g];
+  }
+  return FCP_OK;
+}

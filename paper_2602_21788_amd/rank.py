@@ -108,6 +108,23 @@ class RankAttention:
         B.fcp_attn_fwd_step(self.q, self.k, self.v, self.cu_d, self.work_d, self.n_parts, self.scale,
                             self.o_part, self.lse_part, self.scratch_f, stream)
 
+    def forward_running(self, stream=None):
+        """The forward pass as one fcp_attn_fwd_step_running call per ring step (no partials, no merge): the
+        results land in self.o (bf16), self.lse and self.o_run (fp32)."""
+        if not hasattr(self, "step_work_d"):
+            self.step_work_d = []
+            for s in range(self.n_parts):
+                w = np.ascontiguousarray(self.work[self.work["step"] == s])
+                if len(w):
+                    self.step_work_d.append(torch.from_numpy(w.view(np.uint8).copy()).to(self.device))
+            self.o_run = torch.empty(self.tq, self.hq, self.D, dtype=torch.float32, device=self.device)
+        self.o_run.zero_()
+        self.lse.fill_(float("-inf"))
+        self.o.zero_()
+        for w in self.step_work_d:
+            B.fcp_attn_fwd_step_running(self.q, self.k, self.v, self.cu_d, w, self.scale, self.o_run, self.lse,
+                                        self.scratch_f, o_out=self.o, q_limit=self.q_limit_d, stream=stream)
+
     def merge(self, stream=None):
         B.fcp_lse_merge(self.o_part, self.lse_part, self.o, self.lse, stream)
 

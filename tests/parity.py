@@ -26,13 +26,14 @@ def bf16_tensor_to_f64(t):
     return synth.bf16_bits_to_f64(t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
 
 
-def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label="", spans=None):
+def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label="", spans=None, base_rank=None):
     """Full element-by-element comparison of one rank (small workloads).  spans: full-attention spans
     [(seq, start, len), ...] of a mixed mask, None = causal."""
     import torch
     from paper_2602_21788_amd.rank import RankAttention
-    ra = RankAttention(wl.seq_lens, wl.cp_degree, rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
-    ochunks, owork = oplan.shard_plan(wl.seq_lens, wl.cp_degree, spans=spans)
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans,
+                       base_rank=base_rank)
+    ochunks, owork = oplan.shard_plan(wl.seq_lens, wl.cp_degree, base_rank, spans=spans)
     sid = None if spans is None else oplan.span_ids(wl.seq_lens, spans)
     assert ra.chunks.tobytes() == ochunks.tobytes() and ra.work_all.tobytes() == owork.tobytes()
     rows = oplan.rank_rows(ochunks, wl.cu_seqlens, rank)

@@ -122,6 +122,32 @@ def test_cfg2_full_size_sampled():
         assert e["dK"] <= TOL_BF16_REL and e["dV"] <= TOL_BF16_REL
 
 
+def test_planned_microbatch_atomic_groups_end_to_end():
+    """Scheduler to kernels: fcp_plan_groups packs a micro-batch into atomic groups and gives them degrees, every
+    sequence then runs at its GROUP's degree on the group's ranks (the paper's execution of an atomic group: short
+    sequences are sharded too), fcp_shard_plan splits them, and every rank's attention matches the oracle; the ranks'
+    dK/dV partial sums add up to the unsharded gradient."""
+    import paper_2602_21788_amd as fcp
+    lens = [3000, 700, 300, 260, 90, 40, 1500]
+    n_ranks, cap = 6, 1024
+    plan = fcp.fcp_plan_groups(lens, n_ranks, cap, (1e-9, 1e-7, 1e-5, 0.0, 0.0))
+    deg, base = fcp.fcp_group_shard_args(plan["group_of_seq"], plan["degree"], plan["base_rank"])
+    _say(f"planned micro-batch: groups {plan['group_of_seq'].tolist()} degrees {plan['degree'].tolist()} "
+         f"-> per-sequence degree {deg.tolist()} base {base.tolist()}")
+    assert plan["degree"].sum() <= n_ranks and deg[0] >= 3 and (deg[np.array(lens) < 100] > 1).any()
+    wl = synth.custom_workload(lens, deg, hq=4, hkv=2, head_dim=128, seed=55)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    dK_sum = dV_sum = None
+    for r in range(int(plan["degree"].sum())):
+        res = check_rank(wl, q, k, v, do, r, backward=True, check_partials=True, label=f"planned r{r}", base_rank=base)
+        if res is None:
+            continue
+        dK_sum = res["_dK_acc"] if dK_sum is None else dK_sum + res["_dK_acc"]
+        dV_sum = res["_dV_acc"] if dV_sum is None else dV_sum + res["_dV_acc"]
+    _, dK_ref, dV_ref = oattn.attn_bwd(q, k, v, do, wl.cu_seqlens, wl.softmax_scale)
+    assert rel_err(dK_sum, dK_ref) <= TOL_BF16_REL and rel_err(dV_sum, dV_ref) <= TOL_BF16_REL
+
+
 def test_profiler_fits_measured_attention_times():
     """The scheduler's Profiler on this library's own kernels: fit Eq. 8's compute model to measured forward + backward
     times of single sequences and plan a micro-batch with it (the paper reports estimation errors below 8 %; the
@@ -135,3 +161,43 @@ def test_profiler_fits_measured_attention_times():
     assert a1 > 0 and err < 0.25
     plan = fcp.fcp_plan_groups([16384, 4096, 4096, 2048], 8, 8192, (a1, max(a2, 0.0), max(b1, 0.0), 0.0, 0.0))
     assert plan["d_min"][0] == 2 and plan["degree"][0] >= plan["degree"][1] and sum(plan["degree"]) <= 8
+
+
+@pytest.mark.parametrize("case", ["d3_packed", "d5_all_ranks", "shorts_D64", "mixed_mask"])
+def test_running_merge_forward_equals_partial_plus_merge(case):
+    """fcp_attn_fwd_step_running, one call per ring step with no partial results, against the oracle and against
+    the partial + merge pair (same kernels, same tiles: O within one bf16 rounding, LSE to 1e-5)."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    from oracle import plan as oplan
+    from parity import TOL_LSE_ABS, bf16_tensor_to_f64
+    spans = None
+    if case == "d3_packed":
+        wl = synth.custom_workload([2100, 75, 640], [3, 1, 2], hq=8, hkv=2, head_dim=128, seed=61); ranks = [0, 2]
+    elif case == "d5_all_ranks":
+        wl = synth.custom_workload([1777], [5], hq=4, hkv=4, head_dim=128, seed=62); ranks = range(5)
+    elif case == "shorts_D64":
+        wl = synth.custom_workload([1, 130, 64, 257, 33, 511], [1] * 6, hq=6, hkv=2, head_dim=64, seed=63); ranks = [0]
+    else:
+        wl = synth.custom_workload([1500, 300], [3, 1], hq=4, hkv=2, head_dim=128, seed=64); ranks = range(3)
+        spans = [(0, 200, 330), (0, 700, 64), (0, 990, 30), (1, 10, 200)]
+    q, k, v, do = synth.draw_qkvdo(wl)
+    sid = None if spans is None else oplan.span_ids(wl.seq_lens, spans)
+    ochunks, _ = oplan.shard_plan(wl.seq_lens, wl.cp_degree, spans=spans)
+    for r in ranks:
+        _say(f"running merge: {case} rank {r}")
+        ra = RankAttention(wl.seq_lens, wl.cp_degree, r, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
+        ra.set_inputs(q, k, v, do)
+        ra.forward()
+        torch.cuda.synchronize()
+        o_ref_path, lse_ref_path = bf16_tensor_to_f64(ra.o), ra.lse.cpu().numpy().astype(np.float64)
+        ra.forward_running()
+        torch.cuda.synchronize()
+        O, LSE = bf16_tensor_to_f64(ra.o), ra.lse.cpu().numpy().astype(np.float64)
+        rows = oplan.rank_rows(ochunks, wl.cu_seqlens, r)
+        O_ref, LSE_ref = oattn.attn_fwd(q, k, v, wl.cu_seqlens, wl.softmax_scale, rows, span_id=sid)
+        assert np.isfinite(O).all() and np.isfinite(LSE).all()
+        assert rel_err(O, O_ref) <= TOL_BF16_REL and np.abs(LSE.T - LSE_ref).max() <= TOL_LSE_ABS
+        assert np.abs(LSE - lse_ref_path).max() <= 1e-5
+        assert np.abs(O - o_ref_path).max() <= 2.0 ** -7 * max(1.0, np.abs(o_ref_path).max())
+        assert rel_err(ra.o_run.cpu().numpy().astype(np.float64), O_ref) <= 1e-2     # the fp32 running result itself

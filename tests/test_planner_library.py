@@ -94,3 +94,38 @@ def test_profiler_fit_recovers_coefficients():
     noisy = t * (1 + 0.03 * rng.standard_normal(24))
     (g1, _, _), _ = profiler.fit_compute_coefficients(lens, deg, noisy)
     assert g1 == pytest.approx(a1, rel=0.1)          # the quadratic term dominates and survives 3 % noise
+
+
+def test_group_shard_args_and_rank_coverage():
+    """Every sequence takes its group's degree and base rank (the paper's atomic groups); the shard plan built from them
+    places every token on exactly one rank of its group, and no rank holds more tokens than its budget allows."""
+    from oracle import plan as oplan
+    rng = np.random.default_rng(11)
+    for trial in range(30):
+        lens = [int(x) for x in rng.integers(16, 9000, size=int(rng.integers(1, 12)))]
+        n_ranks, cap = 16, 4096
+        cm = (1e-9, 1e-6, 1e-4, 2e-7, 1e-4)
+        try:
+            plan = B.fcp_plan_groups(lens, n_ranks, cap, cm)
+        except B.FcpError:
+            continue
+        oplan_res = op.plan(lens, n_ranks, cap, op.CostModel(*cm))
+        deg, base = B.fcp_group_shard_args(plan["group_of_seq"], plan["degree"], plan["base_rank"])
+        odeg, obase = op.group_shard_args(oplan_res)
+        assert list(deg) == odeg and list(base) == obase
+        chunks, _ = B.fcp_shard_plan(lens, deg, base)
+        per_rank = np.zeros(n_ranks, np.int64)
+        for c in chunks:
+            g = plan["group_of_seq"][c["seq"]]
+            assert plan["base_rank"][g] <= c["rank"] < plan["base_rank"][g] + plan["degree"][g]
+            per_rank[c["rank"]] += c["len"]
+        assert per_rank.sum() == sum(lens)
+        # an even split of every sequence of a group over its d ranks: at most ceil-rounding above load / d,
+        # one token per chunk pair and sequence
+        for g in range(len(plan["degree"])):
+            seqs = [k for k in range(len(lens)) if plan["group_of_seq"][k] == g]
+            load, d = sum(lens[k] for k in seqs), int(plan["degree"][g])
+            ranks = per_rank[plan["base_rank"][g]: plan["base_rank"][g] + d]
+            assert ranks.max() <= load / d + 2 * len(seqs) and ranks.max() <= cap + 2 * len(seqs)
+    with pytest.raises(B.FcpError):
+        B.fcp_group_shard_args([0, 2], [1, 1], [0, 1])
