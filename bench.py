@@ -70,6 +70,10 @@ def main():
     ap.add_argument("--mask", choices=["causal", "mixed"], default="causal",
                     help="mixed: the same workload with synthetic image spans (576 tokens each, about 35 %% of a "
                          "sequence) that attend in full; pairs and flops then count the pairs visible under that mask")
+    ap.add_argument("--forward", choices=["partial", "running"], default="partial",
+                    help="running: the forward pass as one fcp_attn_fwd_step_running call per ring step (no partial "
+                         "results, no fcp_lse_merge) instead of fcp_attn_fwd_step + fcp_lse_merge; a comparison, not "
+                         "the headline path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy after the timed steps: the reference dispatch for scaling "
@@ -104,8 +108,12 @@ def main():
         def mark(i):
             if events is not None:
                 events[i].record()
-        mark(0); ra.forward_steps()
-        mark(1); ra.merge()
+        if args.forward == "running":
+            mark(0); ra.forward_running()
+            mark(1)
+        else:
+            mark(0); ra.forward_steps()
+            mark(1); ra.merge()
         mark(2); ra.zero_grads()
         mark(3); ra.backward_delta()
         mark(4); ra.backward_steps()
@@ -138,7 +146,7 @@ def main():
         "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl_name, "mask": args.mask, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
+        "config": {"workload": wl_name, "mask": args.mask, "forward": args.forward, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
                    "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
                    "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
                    "seed": wl.seed},

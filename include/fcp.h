@@ -223,7 +223,8 @@ int fcp_attn_bwd_step_mixed(const void* q, const void* k, const void* v, const v
  *   LSE' = ln(exp(LSE) + sum_j exp(s_j)),  O' = (exp(LSE - LSE') O + sum_j exp(s_j - LSE') V_j).
  * Inside the kernel the previous result simply is the initial state of the online softmax.
  *   o_run [tq,hq,D] fp32, lse_run [hq,tq] fp32 device, in/out.  Before the first step the caller sets lse_run
- *         to -inf and o_run to 0.  Rows that no item of the call covers are left as they are.
+ *         to -inf (o_run of a row with lse_run = -inf is not read).  Rows that no item of the call covers are
+ *         left as they are.
  *   o_out [tq,hq,D] bf16 device or NULL: the covered rows' O' rounded to bf16 as well (pass it in every call, or
  *         at least in the last call that covers a row: a row's last visit may come before the last ring step)
  *   q_limit: NULL (causal) or as in fcp_attn_fwd_step_mixed.  The items' `step` fields are ignored.

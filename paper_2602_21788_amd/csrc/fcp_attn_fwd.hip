@@ -229,7 +229,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     if (p.running) {
       // The caller's merged result of the earlier ring steps is one more block of keys already folded into the
       // state: maximum = its LSE, sum 1 (held by the lower half-wave), accumulator = its normalised O.  A row
-      // without earlier keys (LSE = -inf, O = 0 by contract) starts like any other.
+      // without earlier keys (LSE = -inf) starts like any other.
       const float lse_prev = p.lse_part[(int64_t)head * p.tq + t.q_row0 + row_ld];
       const int row_bytes = p.hq * D * 4;
       const int n_wave_rows = t.rows - wave_r0;
@@ -243,11 +243,22 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
         for (int i = 0; i < 16; ++i)
           oacc[db][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
               ri, o_voff, (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db, 0));
-      if (lse_prev > -INFINITY) {
+      const bool has_prev = lse_prev > -INFINITY;
+      if (has_prev) {
         m_run = lse_prev * kLog2e;
         l_run = g2 == 0 ? 1.f : 0.f;
       }
       __builtin_amdgcn_s_waitcnt(kWaitVm0);   // not inside the tile loop, where a wait would also cover the fills
+      // whatever o_run holds for a row without earlier keys is dropped (the flag travels like a row factor)
+      s_rowf[wave][l32] = has_prev ? 1.f : 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const f32x4 a = *reinterpret_cast<const f32x4*>(&s_rowf[wave][8 * j + 4 * g2]);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) oacc[db][4 * j + e] = a[e] != 0.f ? oacc[db][4 * j + e] : 0.f;
+      }
     }
     f32x16 sacc[2];            // scores of the current tile: sacc[kb][i] = key 32 kb + 8 (i/4) + 4 g2 + (i%4), query l32
     bf16x8 pf[4];              // P^T of the current tile as B operands: k-step tt covers keys 16 tt .. 16 tt + 15

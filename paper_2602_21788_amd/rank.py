@@ -118,9 +118,7 @@ class RankAttention:
                 if len(w):
                     self.step_work_d.append(torch.from_numpy(w.view(np.uint8).copy()).to(self.device))
             self.o_run = torch.empty(self.tq, self.hq, self.D, dtype=torch.float32, device=self.device)
-        self.o_run.zero_()
         self.lse.fill_(float("-inf"))
-        self.o.zero_()
         for w in self.step_work_d:
             B.fcp_attn_fwd_step_running(self.q, self.k, self.v, self.cu_d, w, self.scale, self.o_run, self.lse,
                                         self.scratch_f, o_out=self.o, q_limit=self.q_limit_d, stream=stream)
