@@ -201,3 +201,49 @@ def test_running_merge_forward_equals_partial_plus_merge(case):
         assert np.abs(LSE - lse_ref_path).max() <= 1e-5
         assert np.abs(O - o_ref_path).max() <= 2.0 ** -7 * max(1.0, np.abs(o_ref_path).max())
         assert rel_err(ra.o_run.cpu().numpy().astype(np.float64), O_ref) <= 1e-2     # the fp32 running result itself
+
+
+def test_whole_path_in_a_hip_graph_replays_identically():
+    """The library calls enqueue kernels only (no allocation, no host synchronisation, no memset nodes), so the whole
+    path of a rank can be captured into a HIP graph.  The graph is replayed three times with eager work and
+    synchronisations in between and fresh inputs before every replay; every replay must reproduce the eager result of
+    the same inputs (bit for bit where no atomics are involved: O, LSE, dQ of exclusive rows; to 1e-6 relative for
+    the fp32 accumulators that several work items add to)."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    wl = synth.custom_workload([1300, 200, 650], [3, 1, 2], hq=8, hkv=2, head_dim=128, seed=71)
+    ra = RankAttention(wl.seq_lens, wl.cp_degree, 0, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
+    ra.set_random_inputs(seed=1)
+
+    def whole_path():
+        ra.forward()
+        ra.backward()
+
+    whole_path()                       # eager warm-up: the kernels' LDS limits are raised outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        whole_path()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            whole_path()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device=ra.device).manual_seed(123)
+    for replay in range(3):
+        for t in (ra.q, ra.k, ra.v, ra.d_o):      # new inputs in the same buffers
+            t.copy_(torch.randn(t.shape, generator=gen, device=ra.device, dtype=torch.float32).to(torch.bfloat16))
+        for t in (ra.o, ra.lse, ra.dq, ra.dk, ra.dv):
+            t.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (ra.o, ra.lse, ra.dq, ra.dk, ra.dv)]
+        whole_path()                   # eager, same inputs
+        torch.cuda.synchronize()
+        want = [ra.o, ra.lse, ra.dq, ra.dk, ra.dv]
+        _say(f"graph replay {replay}: max |diff| " + ", ".join(f"{(a.float() - b.float()).abs().max().item():.2e}" for a, b in zip(got, want)))
+        assert torch.equal(got[0], want[0]) and torch.equal(got[1], want[1])
+        for a, b in zip(got[2:], want[2:]):
+            assert torch.isfinite(a.float()).all()
+            assert (a.float() - b.float()).abs().max().item() <= 1e-2 * b.float().abs().max().item()
