@@ -61,6 +61,41 @@ def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30, spans=None):
                       f"fwd + dQ + dK/dV partial, {pairs} pairs, {dt:.1f} s"}
 
 
+def degree_sweep(steps, warmup):
+    """One 32768-token sequence at CP degrees 1..8: what rank 0 does per layer (all ring steps of its two zigzag
+    chunks, merge, backward), device-side random inputs."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    rows = []
+    for d in range(1, 9):
+        ra = RankAttention([32768], [d], 0, 32, 8, 128)
+        ra.set_random_inputs(seed=d)
+        pairs = ra.pairs()
+        for _ in range(warmup):
+            ra.forward(); ra.backward()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        tf, tm, tb = [], [], []
+        for _ in range(steps):
+            ev[0].record(); ra.forward_steps(); ev[1].record(); ra.merge(); ev[2].record()
+            ra.zero_grads(); ra.backward_delta(); torch.cuda.synchronize()
+            ev[0].synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); ra.backward_steps(); b.record(); torch.cuda.synchronize()
+            tf.append(ev[0].elapsed_time(ev[1])); tm.append(ev[1].elapsed_time(ev[2])); tb.append(a.elapsed_time(b))
+        f, m, b = float(np.median(tf)), float(np.median(tm)), float(np.median(tb))
+        fl = pairs * 128.0 * 32.0
+        rows.append({"degree": d, "rank": 0, "rank_rows": ra.tq, "pairs": pairs, "n_parts": ra.n_parts,
+                     "fwd_step_ms": f, "merge_ms": m, "bwd_step_ms": b,
+                     "fwd_tflops": 4.0 * fl / (f * 1e-3) / 1e12, "bwd_tflops": 10.0 * fl / (b * 1e-3) / 1e12,
+                     "fwd_frac_mfma_peak": 4.0 * fl / (f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                     "bwd_frac_mfma_peak": 10.0 * fl / (b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+        del ra
+        torch.cuda.empty_cache()
+    return {"metric": "rank-local varlen causal attn TFLOP/s, CP degree sweep on one 32768-token sequence",
+            "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "L32768_d1to8_h32x8_D128", "rank": 0}, "sweep": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -74,6 +109,9 @@ def main():
                     help="running: the forward pass as one fcp_attn_fwd_step_running call per ring step (no partial "
                          "results, no fcp_lse_merge) instead of fcp_attn_fwd_step + fcp_lse_merge; a comparison, not "
                          "the headline path")
+    ap.add_argument("--degree-sweep", action="store_true",
+                    help="secondary table instead of the benchmark line: one 32768-token sequence at CP degrees 1..8 "
+                         "(rank 0's share, 32 / 8 heads, D = 128), forward and backward step times and rates")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy after the timed steps: the reference dispatch for scaling "
@@ -92,6 +130,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.degree_sweep:
+        print(json.dumps(degree_sweep(args.steps, args.warmup)))
+        return
     wl = synth.make_workload(args.workload)
     q, k, v, do = synth.draw_qkvdo(wl)
     spans = synth.image_spans(wl.seq_lens, wl.seed) if args.mask == "mixed" else None
