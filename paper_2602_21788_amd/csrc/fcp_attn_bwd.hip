@@ -440,12 +440,14 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
   float* stats = reinterpret_cast<float*>(static_cast<char*>(region_q) + fcp::sched_region_bytes(n_work, cap_q));
-  int rc = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
+  if (tq == 0 || n_work == 0) {     // nothing to add; the lists are still built so that the status call works
+    int rc0 = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
+    if (rc0 != FCP_OK) return rc0;
+    return fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
+  }
+  int rc = fcp::launch_schedule_bwd((int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv,
+                                    cap_kv, region_kv, cap_q, region_q, lse, delta, (int64_t)hq * tq, stats, st);
   if (rc != FCP_OK) return rc;
-  rc = fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
-  if (rc != FCP_OK) return rc;
-  if (tq == 0 || n_work == 0) return FCP_OK;
-  if ((rc = fcp::launch_row_stats(lse, delta, (int64_t)hq * tq, stats, st)) != FCP_OK) return rc;
 
   fcp::BwdParams p;
   p.q = (const uint16_t*)q; p.k = (const uint16_t*)k; p.v = (const uint16_t*)v; p.d_o = (const uint16_t*)d_o;

@@ -456,28 +456,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
   pt.end(p.hdr);
 }
 
-// Row statistics in the form the kernels consume: plane 0 = -LSE log2 e (-inf for a row without keys, so that
-// its probabilities vanish), plane 1 = -delta.
-__global__ __launch_bounds__(256) void row_stats_kernel(const float* __restrict__ lse, const float* __restrict__ delta,
-                                                        int64_t n, float* __restrict__ stats) {
-  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
-    const float l = lse[i];
-    stats[i] = l == -INFINITY ? -INFINITY : -l * kLog2e;
-    stats[n + i] = -delta[i];
-  }
-}
-
 }  // namespace
-
-int launch_row_stats(const float* lse, const float* delta, int64_t n, float* stats, hipStream_t stream) {
-  if (n <= 0) return FCP_OK;
-  int64_t blocks = (n + 255) / 256;
-  if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(row_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, lse, delta, n, stats);
-  FCP_HIP_CHECK(hipGetLastError());
-  return FCP_OK;
-}
 
 int launch_dkv(const BwdParams& p, int head_dim, int64_t units, int n_cu, hipStream_t stream) {
   int64_t blocks = n_cu;                               // one 1024-thread block per CU

@@ -23,9 +23,6 @@ struct BwdParams {
   float scale, scale_log2;
 };
 
-// Row statistics in the form the backward kernels consume, written once per backward step.
-int launch_row_stats(const float* lse, const float* delta, int64_t n, float* stats, hipStream_t stream);
-
 // dK / dV over key tiles (csrc/fcp_attn_dkv.hip).  `units` = upper bound of (key tile, KV head) units.
 int launch_dkv(const BwdParams& p, int head_dim, int64_t units, int n_cu, hipStream_t stream);
 

@@ -126,18 +126,12 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32
   return base + inc - v;
 }
 
-__global__ __launch_bounds__(kSchedThreads) void sched_kernel(
+// One tile list, built by one block.
+__device__ void build_list(
     int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
     const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
-    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
-    float* lse_fill, int64_t lse_fill_n) {
-  if (blockIdx.x > 0) {  // the other blocks pre-fill the partial LSE with -inf
-    const int64_t stride = (int64_t)(gridDim.x - 1) * kSchedThreads;
-    for (int64_t i = (int64_t)(blockIdx.x - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
-      lse_fill[i] = -INFINITY;
-    return;
-  }
+    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles) {
   __shared__ int32_t s_wave[kSchedThreads / 64];
   __shared__ int32_t s_hist[kBuckets];
   __shared__ int32_t s_max, s_rej, s_carry;
@@ -297,6 +291,53 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
   }
 }
 
+// Forward: block 0 builds the query-tile list, the other blocks pre-fill the partial LSE with -inf.
+__global__ __launch_bounds__(kSchedThreads) void sched_kernel(
+    int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
+    const fcp_work_desc* __restrict__ work, int32_t n_work,
+    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
+    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
+    float* lse_fill, int64_t lse_fill_n) {
+  if (blockIdx.x > 0) {
+    const int64_t stride = (int64_t)(gridDim.x - 1) * kSchedThreads;
+    for (int64_t i = (int64_t)(blockIdx.x - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
+      lse_fill[i] = -INFINITY;
+    return;
+  }
+  build_list(backward, check_step, tile, inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, n_parts, tile_cap,
+             hdr, item_off, item_flags, tiles);
+}
+
+// Backward: one launch for everything that precedes the two attention kernels.  Block 0 builds the key-tile list
+// (dK/dV kernel), block 1 the query-tile list (dQ kernel), the other blocks write the row statistics in the form
+// the kernels consume: plane 0 = -LSE log2 e (-inf for a row without keys, so that its probabilities vanish),
+// plane 1 = -delta.
+struct ListJob {
+  int32_t tile, inner, tile_cap;
+  SchedHeader* hdr;
+  int32_t* item_off;
+  int32_t* item_flags;
+  Tile* tiles;
+};
+__global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
+    const ListJob kv, const ListJob qt, int32_t max_seg_keys, const MaskTables m,
+    const fcp_work_desc* __restrict__ work, int32_t n_work,
+    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv,
+    const float* __restrict__ lse, const float* __restrict__ delta, int64_t n_stats, float* __restrict__ stats) {
+  if (blockIdx.x >= 2) {
+    const int64_t stride = (int64_t)(gridDim.x - 2) * kSchedThreads;
+    for (int64_t i = (int64_t)(blockIdx.x - 2) * kSchedThreads + threadIdx.x; i < n_stats; i += stride) {
+      const float l = lse[i];
+      stats[i] = l == -INFINITY ? -INFINITY : -l * 1.4426950408889634f;
+      stats[n_stats + i] = -delta[i];
+    }
+    return;
+  }
+  const ListJob& j = blockIdx.x == 0 ? kv : qt;
+  build_list(blockIdx.x == 0 ? 1 : 0, 0, j.tile, j.inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, 1,
+             j.tile_cap, j.hdr, j.item_off, j.item_flags, j.tiles);
+}
+
 }  // namespace
 
 int64_t q_tile_cap(int32_t tq, int32_t tkv, int64_t n_work, int32_t n_parts) {
@@ -330,6 +371,30 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
                      backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner,
                      (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
                      (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n);
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}
+
+int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from,
+                        const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                        int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
+                        const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream) {
+  auto job = [&](void* region, int32_t tile, int32_t inner, int64_t cap) {
+    ListJob j;
+    j.tile = tile; j.inner = inner; j.tile_cap = (int32_t)cap;
+    j.hdr = reinterpret_cast<SchedHeader*>(region);
+    j.item_off = reinterpret_cast<int32_t*>(static_cast<char*>(region) + sizeof(SchedHeader));
+    j.item_flags = const_cast<int32_t*>(sched_flags(region, n_work));
+    j.tiles = const_cast<Tile*>(sched_tiles(region, n_work));
+    return j;
+  };
+  int64_t stat_blocks = (n_stats + kSchedThreads * 4 - 1) / (kSchedThreads * 4);
+  if (stat_blocks > 1024) stat_blocks = 1024;
+  if (stat_blocks < 1) stat_blocks = 1;
+  hipLaunchKernelGGL(sched_bwd_kernel, dim3((unsigned)(2 + stat_blocks)), dim3(kSchedThreads), 0, stream,
+                     job(region_kv, kBwdBN, kBwdBM, cap_kv), job(region_q, kDqBM, kDqBN, cap_q),
+                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work,
+                     (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, lse, delta, n_stats, stats);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
 }
