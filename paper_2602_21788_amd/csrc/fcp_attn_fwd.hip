@@ -53,7 +53,7 @@ struct FwdParams {
 };
 
 constexpr float kRescaleThreshold = 8.f;   // log2 units
-constexpr int kFwdAhead = 4;               // LDS fragments requested this many MFMAs before their use
+constexpr int kFwdAhead = 4;               // LDS fragments requested this many MFMAs before their use (3 and 6 measured: no better)
 
 template <int D>
 struct FwdCfg {
@@ -274,34 +274,55 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       const int tt = g / C::NVA, db = g % C::NVA;
       return tr_read_8(smem + va[db] + tt * (16 * VT::row_base(1)), 8 * VT::row_base(1));
     };
-    // Matrix slot of step `it`: scores of tile it (if DO_S), O += P V of tile it - 1 (if DO_PV).  The order
-    // is written out MFMA by MFMA and fenced so that every LDS fragment is requested kAhead MFMAs before the
-    // one that consumes it.
-    auto matrix_slot = [&](auto do_s_c, auto do_pv_c, int it) {
-      constexpr bool DO_S = decltype(do_s_c)::value, DO_PV = decltype(do_pv_c)::value;
-      constexpr int N1 = DO_S ? 2 * C::NS : 0, N2 = DO_PV ? 4 * C::NVA : 0, N = N1 + N2, kAhead = kFwdAhead;
-      int ka[C::NKA], va[C::NVA];
-      const int koff = (it & (C::NSTAGE - 1)) * C::STAGE, voff = ((it - 1) & (C::NSTAGE - 1)) * C::STAGE;
-#pragma unroll
-      for (int j = 0; j < C::NKA; ++j) ka[j] = kaddr[j] + koff;
+    // Matrix slot of step `it`: scores of tile it (score_part), O += P V of tile it - 1 (pv_part), each present ONCE in
+    // the program and run or skipped as a whole.  (Variants of the slot that repeat the second contraction on several
+    // paths make the register allocator keep two copies of the O accumulator and move 64 registers between them in
+    // every step.)  The order inside a part is written out MFMA by MFMA and fenced so that every LDS fragment is
+    // requested kAhead MFMAs before the one that consumes it; the first fragments of the second contraction are
+    // requested before the scores (pv_head), so that it starts without waiting for LDS.
+    constexpr int kAhead = kFwdAhead;
+    bf16x8 vhead[kAhead];
+    auto pv_head = [&](int it) {
+      int va[C::NVA];
+      const int voff = ((it - 1) & (C::NSTAGE - 1)) * C::STAGE;
 #pragma unroll
       for (int db = 0; db < C::NVA; ++db) va[db] = vaddr[db] + voff;
-      bf16x8 fr[N > 0 ? N : 1];
-      auto request = [&](int x) {
-        if (x < N1) fr[x] = k_frag(ka, x);
-        else if (x < N) fr[x] = v_frag(va, x - N1);
-      };
+#pragma unroll
+      for (int x = 0; x < kAhead; ++x) vhead[x] = v_frag(va, x);
+    };
+    auto score_part = [&](int it) {
+      constexpr int N = 2 * C::NS;
+      int ka[C::NKA];
+      const int koff = (it & (C::NSTAGE - 1)) * C::STAGE;
+#pragma unroll
+      for (int j = 0; j < C::NKA; ++j) ka[j] = kaddr[j] + koff;
+      bf16x8 fr[N];
+      auto request = [&](int x) { if (x < N) fr[x] = k_frag(ka, x); };
 #pragma unroll
       for (int x = 0; x < kAhead; ++x) request(x);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int x = 0; x < N; ++x) {
-        if (x < N1) {
-          sacc[x / C::NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], qf[x % C::NS], x % C::NS == 0 ? zero16() : sacc[x / C::NS], 0, 0, 0);
-        } else {
-          const int g = x - N1;
-          oacc[g % C::NVA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[g / C::NVA], fr[x], oacc[g % C::NVA], 0, 0, 0);
-        }
+        sacc[x / C::NS] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], qf[x % C::NS], x % C::NS == 0 ? zero16() : sacc[x / C::NS], 0, 0, 0);
+        request(x + kAhead);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    auto pv_part = [&](int it) {
+      constexpr int N = 4 * C::NVA;
+      static_assert(kAhead <= N, "the head fragments are all used");
+      int va[C::NVA];
+      const int voff = ((it - 1) & (C::NSTAGE - 1)) * C::STAGE;
+#pragma unroll
+      for (int db = 0; db < C::NVA; ++db) va[db] = vaddr[db] + voff;
+      bf16x8 fr[N];
+#pragma unroll
+      for (int x = 0; x < kAhead; ++x) fr[x] = vhead[x];
+      auto request = [&](int x) { if (x < N) fr[x] = v_frag(va, x); };
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int x = 0; x < N; ++x) {
+        oacc[x % C::NVA] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[x / C::NVA], fr[x], oacc[x % C::NVA], 0, 0, 0);
         request(x + kAhead);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -375,8 +396,6 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();                       // tiles 0 and 1 have landed
     if (grp == 1) __syncthreads();
-    using T = std::true_type;
-    using F = std::false_type;
     for (int it = 0; it <= n_iter; ++it) {
       pt.mark(0);
       fill_next();
@@ -385,9 +404,9 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       // the matrix stream goes first at the SIMD's issue port: an MFMA is wanted every 32 cycles and must not
       // queue behind the partner wave's vector instructions
       __builtin_amdgcn_s_setprio(3);
-      if (do_s && do_pv) matrix_slot(T{}, T{}, it);
-      else if (do_s) matrix_slot(T{}, F{}, it);
-      else if (do_pv) matrix_slot(F{}, T{}, it);
+      if (do_pv) pv_head(it);
+      if (do_s) score_part(it);
+      if (do_pv) pv_part(it);
       __builtin_amdgcn_s_setprio(0);
       pt.mark(2);
       boundary();

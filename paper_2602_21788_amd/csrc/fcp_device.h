@@ -89,9 +89,11 @@ __device__ inline uint32_t lds_offset(const void* p) {
 // Written in assembly so that the compiler does not count it among the LDS stores it orders LDS reads
 // after (it would make the wave wait for the load just issued before its next LDS read); the caller waits
 // with s_waitcnt vmcnt and a barrier before anybody reads the tile.  `lds` and `soff` must be wave-uniform.
-// M0 is not used by anything else in these kernels.
+// M0 is not used by anything else in these kernels.  The s_nop covers the wait states between the write of M0 and the
+// load and, with the s_mov, the five a vector memory instruction needs after a v_readlane that restored one of its
+// scalar operands (the compiler pads its own instructions for that hazard, not the inside of an assembly statement).
 __device__ inline void lds_fill_b128(i32x4 rsrc, uint32_t lds, int voff, int soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
                :: "s"(__builtin_amdgcn_readfirstlane((int)lds)), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
@@ -132,7 +134,7 @@ struct DualTile {
 
 // One wave-wide LDS-direct load of one dword per lane: lane L's 4 bytes land at LDS offset lds + 4 L.
 __device__ inline void lds_fill_b32(i32x4 rsrc, uint32_t lds, int voff, int soff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 3\n\tbuffer_load_dword %1, %2, %3 offen lds"
                :: "s"(__builtin_amdgcn_readfirstlane((int)lds)), "v"(voff), "s"(rsrc), "s"(__builtin_amdgcn_readfirstlane(soff)) : "memory");
 }
 
