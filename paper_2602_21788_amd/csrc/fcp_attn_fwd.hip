@@ -74,7 +74,6 @@ struct FwdCfg {
   static constexpr int NVA = D / 32;              // distinct per-lane V^T read addresses
   static constexpr int NS = D / 16;               // MFMAs of one 32 x 32 score block
   static constexpr int KB_STRIDE = KT::row_base(32);
-  static constexpr int kWaitFills = 0x0F70 | FILLS;   // s_waitcnt vmcnt(FILLS)
   static_assert(RPW % KT::RPI == 0 && FILLS < 16, "fill split");
 };
 
@@ -178,8 +177,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     }
     // This wave's share (RPW rows of K and of V, FILLS instructions) of the LDS-direct fill of the NEXT tile in
     // list order into the next stage (tiles are filled strictly in order 0, 1, 2, ...).  Tiles past the end of
-    // the list lie outside the resource's range, load nothing and write zeros; every call issues exactly FILLS
-    // loads, which the vmcnt waits rely on.  The running state keeps the scalar work per call small.
+    // the list lie outside the resource's range, load nothing and write zeros.  The running
+    // state keeps the scalar work per call small.
     i32x4 f_rk = rk[0], f_rv = rv[0];
     int f_left = nt0;                      // tiles left in segment 0 while it is being filled
     bool f_seg0 = true;
@@ -200,11 +199,6 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       f_soff += C::BN * kv_row_bytes;
       f_dst += C::STAGE;
       if (f_dst >= f_dst_end) f_dst -= C::NSTAGE * C::STAGE;
-    };
-    // slot boundary: this wave's fills older than its newest batch have landed, then everybody meets
-    auto boundary = [&]() {
-      __builtin_amdgcn_s_waitcnt(C::kWaitFills);
-      __syncthreads();
     };
 
     // Prologue fills: tiles 0 and 1.  The previous unit's last barrier guarantees that no wave still reads
@@ -390,15 +384,18 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     };
 
     // ---- the unit -------------------------------------------------------------------------------
-    // Step `it` of a wave = matrix slot (fills of tile it+2; scores of tile it; second contraction of tile it-1)
-    // then vector slot (tile it).  Waves 4..7 start one slot late.  A fill overwrites stage (it+2) % 4, whose
-    // previous tile it-2 was last read in matrix slot it-1 of the late waves, which ended before this slot.
+    // Step `it` of a wave = matrix slot (scores of tile it; second contraction of tile it-1) then vector slot (fills
+    // of tile it+2; softmax of tile it).  Waves 4..7 start one slot late.  The fills go out at the start of the
+    // VECTOR slot: the matrix slot is the longer one and every slot lasts as long as the matrix slot of the four waves
+    // that are in it, so nothing else belongs on its path (measured: -2.5 %).  A fill overwrites stage (it+2) % 4,
+    // whose previous tile it-2 was last read in matrix slot it-1 of both halves, two and one slots earlier; a wave
+    // waits for it at the end of its matrix slot it+1, and tile it+2 is first read in matrix slot it+2 of the early
+    // waves, which starts after the late waves' matrix slot it+1 has ended with the same wait.
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
     __syncthreads();                       // tiles 0 and 1 have landed
     if (grp == 1) __syncthreads();
     for (int it = 0; it <= n_iter; ++it) {
       pt.mark(0);
-      fill_next();
       pt.mark(1);
       const bool do_s = it < n_w, do_pv = it > 0 && it - 1 < n_w;
       // the matrix stream goes first at the SIMD's issue port: an MFMA is wanted every 32 cycles and must not
@@ -409,10 +406,13 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       if (do_pv) pv_part(it);
       __builtin_amdgcn_s_setprio(0);
       pt.mark(2);
-      boundary();
+      // slot boundary: this wave's fills (issued a step ago) have landed, then everybody meets
+      __builtin_amdgcn_s_waitcnt(kWaitVm0);
+      __syncthreads();
+      fill_next();
       if (do_s) vector_slot(it);
       pt.mark(3);
-      boundary();
+      __syncthreads();
       pt.mark(4);
     }
     if (grp == 0) __syncthreads();
