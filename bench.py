@@ -2,8 +2,9 @@
 """Benchmark of the FCP rank-local attention hot path on one MI355X.
 
 A "step" is one pass of the whole path for the reported rank of the workload:
-  fcp_attn_fwd_step (all ring steps) -> fcp_lse_merge -> zero grads -> fcp_attn_bwd_delta ->
-  fcp_attn_bwd_step (all ring steps) -> fcp_grad_finalize x3,
+  fcp_attn_fwd_step (all ring steps) -> fcp_lse_merge -> fcp_attn_bwd_delta ->
+  fcp_attn_bwd_step_direct (all ring steps) -> fcp_grad_finalize_direct
+(--backward accumulate: ... -> zero grads -> fcp_attn_bwd_delta -> fcp_attn_bwd_step -> fcp_grad_finalize x3),
 with every input already resident in HBM.  The metric is causal-effective TFLOP/s:
 14 * pairs * head_dim * hq / time (4 forward + 10 backward flops per visible pair, channel
 and head; masked pairs are not counted).  --mask mixed times the same path through the
@@ -28,7 +29,7 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per fcp_attn_bwd_step launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload only.
-MEASURED_BWD_TRAFFIC_BYTES = {"packed32k_lognormal24_h32x8_D128": 5.66e9}
+MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "accumulate"): 5.66e9}
 
 
 def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30, spans=None):
@@ -109,6 +110,10 @@ def main():
                     help="running: the forward pass as one fcp_attn_fwd_step_running call per ring step (no partial "
                          "results, no fcp_lse_merge) instead of fcp_attn_fwd_step + fcp_lse_merge; a comparison, not "
                          "the headline path")
+    ap.add_argument("--backward", choices=["direct", "accumulate"], default="direct",
+                    help="direct (default): fcp_attn_bwd_step_direct + fcp_grad_finalize_direct - rows whose whole "
+                         "gradient comes from one unit of work are written as bf16 by their kernel, nothing is cleared "
+                         "beforehand; accumulate: clear the fp32 accumulators, fcp_attn_bwd_step, convert all of them")
     ap.add_argument("--degree-sweep", action="store_true",
                     help="secondary table instead of the benchmark line: one 32768-token sequence at CP degrees 1..8 "
                          "(rank 0's share, 32 / 8 heads, D = 128), forward and backward step times and rates")
@@ -155,10 +160,16 @@ def main():
         else:
             mark(0); ra.forward_steps()
             mark(1); ra.merge()
-        mark(2); ra.zero_grads()
-        mark(3); ra.backward_delta()
-        mark(4); ra.backward_steps()
-        mark(5); ra.finalize()
+        if args.backward == "direct":
+            mark(2)
+            mark(3); ra.backward_delta()
+            mark(4); ra.backward_steps_direct()
+            mark(5); ra.finalize_direct()
+        else:
+            mark(2); ra.zero_grads()
+            mark(3); ra.backward_delta()
+            mark(4); ra.backward_steps()
+            mark(5); ra.finalize()
         mark(6)
 
     for _ in range(args.warmup):
@@ -187,13 +198,13 @@ def main():
         "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl_name, "mask": args.mask, "forward": args.forward, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
+        "config": {"workload": wl_name, "mask": args.mask, "forward": args.forward, "backward": args.backward, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
                    "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
                    "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
                    "seed": wl.seed},
-        "roofline": {"bound": "mfma", "kernel": f"fcp_attn_bwd_step (dkv_kernel<{wl.head_dim}> + dq_kernel<{wl.head_dim}>)",
+        "roofline": {"bound": "mfma", "kernel": f"{'fcp_attn_bwd_step_direct' if args.backward == 'direct' else 'fcp_attn_bwd_step'} (dkv_kernel<{wl.head_dim}> + dq_kernel<{wl.head_dim}>)",
                      "achieved": bwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get(wl_name)},
+                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get((wl_name, args.backward))},
         "kernels": {
             "fwd_step": {"ms": seg_ms["fwd_step"], "tflops": fwd_tflops, "frac_mfma_peak": fwd_tflops / PEAK_BF16_TFLOPS},
             "bwd_step": {"ms": seg_ms["bwd_step"], "tflops": bwd_tflops, "frac_mfma_peak": bwd_tflops / PEAK_BF16_TFLOPS},

@@ -240,6 +240,38 @@ int fcp_attn_fwd_step_running(const void* q, const void* k, const void* v, const
 /* Cast n fp32 accumulator values to bf16, round to nearest even.  Device pointers. */
 int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, void* stream);
 
+/*
+ * fcp_attn_bwd_step_direct -- the whole backward of a rank in one call, final bf16 results without a pass over all
+ * accumulators.  Same function as fcp_attn_bwd_step (mask as in fcp_attn_bwd_step_mixed when q_limit / k_from are
+ * given, causal when both are NULL), for a work list that carries ALL ring steps (paper Sec. 3.2: a rank's dQ rows
+ * and, after the ring has returned them, its dK/dV rows are the sums over the steps).  Most rows of a packed batch get
+ * their whole result from one unit of work (every sequence that is not sharded, Sec. 4.1): the kernel that computes
+ * such a row writes it as bf16 at once.  Per query row and per pool key:
+ *   - no work item of the call touches it: the result is zero;
+ *   - one work item owns it (no other item of the call covers the same query rows / key segment): written to
+ *     dq_out / dk_out / dv_out directly, the fp32 accumulator row is neither read nor written;
+ *   - otherwise: accumulated in fp32 in dq_acc / dk_acc / dv_acc (this call clears those rows first; the caller need
+ *     not) with atomics.
+ * fcp_grad_finalize_direct then completes the outputs: accumulated rows are converted (round to nearest even),
+ * untouched rows zeroed, directly written rows left alone.  The row states stay in `scratch` between the two calls.
+ *   dq_acc [tq,hq,D], dk_acc, dv_acc [tkv,hkv,D] fp32 device, contents on entry irrelevant, on exit defined only
+ *   for the accumulated rows;  dq_out [tq,hq,D], dk_out, dv_out [tkv,hkv,D] bf16 device, complete after the finalize.
+ * Limits: those of fcp_attn_bwd_step, and n_work <= 1024 (FCP_ERR_UNSUPPORTED beyond: use the accumulating call).
+ * Other arguments, alignment and errors as in fcp_attn_bwd_step; scratch sized with FCP_SCRATCH_BWD.
+ */
+int fcp_attn_bwd_step_direct(const void* q, const void* k, const void* v, const void* d_o,
+                             const float* lse, const float* delta, const int32_t* cu_seqlens_kv,
+                             int32_t n_seqs, const fcp_work_desc* work, int64_t n_work,
+                             int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                             float softmax_scale, const int32_t* q_limit, const int32_t* k_from,
+                             float* dq_acc, float* dk_acc, float* dv_acc, void* dq_out, void* dk_out,
+                             void* dv_out, void* scratch, size_t scratch_bytes, void* stream);
+
+/* Second half of the direct backward: see fcp_attn_bwd_step_direct.  Same scratch, n_work, sizes and stream. */
+int fcp_grad_finalize_direct(const float* dq_acc, const float* dk_acc, const float* dv_acc, void* dq_out,
+                             void* dk_out, void* dv_out, void* scratch, int64_t n_work, int32_t tq,
+                             int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim, void* stream);
+
 /* Coefficients of the scheduler's time model (paper Eq. 8-9), all >= 0, in the caller's time unit. */
 typedef struct fcp_cost_model {
   double alpha1;         /* attention compute per (1 + eta_k) |s_k|^2                         */

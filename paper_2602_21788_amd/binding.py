@@ -27,7 +27,8 @@ SPAN_DTYPE = np.dtype([("seq", "<i4"), ("start", "<i4"), ("len", "<i4")])
 
 EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_plan_groups", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
            "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status",
-           "fcp_group_shard_args", "fcp_attn_fwd_step_running", "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed"]
+           "fcp_group_shard_args", "fcp_attn_fwd_step_running", "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed",
+           "fcp_attn_bwd_step_direct", "fcp_grad_finalize_direct"]
 
 
 class FcpError(RuntimeError):
@@ -81,6 +82,11 @@ def lib() -> ctypes.CDLL:
         L.fcp_attn_bwd_step_mixed.restype = ctypes.c_int
         L.fcp_attn_bwd_step_mixed.argtypes = [P, P, P, P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, F, P, P, P, P, P, P,
                                               SZ, P]
+        L.fcp_attn_bwd_step_direct.restype = ctypes.c_int
+        L.fcp_attn_bwd_step_direct.argtypes = [P, P, P, P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, F, P, P, P, P, P, P,
+                                               P, P, P, SZ, P]
+        L.fcp_grad_finalize_direct.restype = ctypes.c_int
+        L.fcp_grad_finalize_direct.argtypes = [P, P, P, P, P, P, P, I64, I32, I32, I32, I32, I32, P]
         _lib = L
     return _lib
 
@@ -300,6 +306,29 @@ def fcp_attn_bwd_step_mixed(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softm
                                          _dev_ptr(q_limit), _dev_ptr(k_from), _dev_ptr(dq_acc), _dev_ptr(dk_acc),
                                          _dev_ptr(dv_acc), _dev_ptr(scratch), scratch.numel() * scratch.element_size(),
                                          _stream(stream)))
+
+
+def fcp_attn_bwd_step_direct(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softmax_scale, dq_acc, dk_acc, dv_acc,
+                             dq_out, dk_out, dv_out, scratch, q_limit=None, k_from=None, stream=None):
+    """Whole backward of a rank: rows owned by one unit are written to the bf16 outputs at once (see include/fcp.h)."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_bwd_step_direct(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(d_o), _dev_ptr(lse),
+                                          _dev_ptr(delta), _dev_ptr(cu_seqlens_kv), cu_seqlens_kv.numel() - 1,
+                                          _dev_ptr(work), n_work, tq, tkv, hq, hkv, D, float(softmax_scale),
+                                          _dev_ptr(q_limit), _dev_ptr(k_from), _dev_ptr(dq_acc), _dev_ptr(dk_acc),
+                                          _dev_ptr(dv_acc), _dev_ptr(dq_out), _dev_ptr(dk_out), _dev_ptr(dv_out),
+                                          _dev_ptr(scratch), scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_grad_finalize_direct(dq_acc, dk_acc, dv_acc, dq_out, dk_out, dv_out, scratch, n_work, stream=None):
+    """Second half of the direct backward: converts the accumulated rows, zeroes the untouched ones."""
+    tq, hq, D = dq_acc.shape
+    tkv, hkv, _ = dk_acc.shape
+    _check(lib().fcp_grad_finalize_direct(_dev_ptr(dq_acc), _dev_ptr(dk_acc), _dev_ptr(dv_acc), _dev_ptr(dq_out),
+                                          _dev_ptr(dk_out), _dev_ptr(dv_out), _dev_ptr(scratch), int(n_work), tq, tkv, hq,
+                                          hkv, D, _stream(stream)))
 
 
 def fcp_grad_finalize(acc, out_bf16, stream=None):

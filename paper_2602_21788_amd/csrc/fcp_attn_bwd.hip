@@ -315,12 +315,14 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
           n_pair_rows > 0 ? (n_pair_rows - 1) * row_bytes + 32 * C::NVA * 4 : 0, 0x00020000);
       const int acc_voff = 4 * g2 * row_bytes + 4 * l32;
       auto acc_soff = [&](int kb, int db, int i) { return (32 * kb + 8 * (i / 4) + (i % 4)) * row_bytes + 128 * db; };
+      // Direct mode: the unit owns its rows, so nothing is read and the epilogue writes the final bf16 rows.
+      const bool direct = exclusive && p.dq_out != nullptr;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int db = 0; db < C::NVA; ++db) {
           acc[db][kb] = zero16();
-          if (exclusive) {
+          if (exclusive && !direct) {
 #pragma unroll
             for (int i = 0; i < 16; ++i)
               acc[db][kb][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(racc, acc_voff, acc_soff(kb, db, i), 0));
@@ -328,7 +330,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         }
       // (explicit wait: see the note at the P / dS waves' loads)
       __builtin_amdgcn_s_waitcnt(0x0F70);
-      if (exclusive) {
+      if (exclusive && !direct) {
         const float inv_scale = 1.f / p.scale;
 #pragma unroll
         for (int db = 0; db < C::NVA; ++db)
@@ -382,17 +384,36 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
           }
       }
       pt.mark(2);
-      // epilogue: dQ [query x channel] * scale -> accumulator rows
+      // epilogue: dQ [query x channel] * scale -> accumulator rows (or, in direct mode, the final bf16 rows: half a
+      // line per store)
+      if (direct) {
+        const int out_row_bytes = p.hq * D * 2;
+        const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(p.dq_out + ((int64_t)(t.q_row0 + 64 * qp) * p.hq + head) * D + 32 * C::NVA * ch), (short)0,
+            n_pair_rows > 0 ? (n_pair_rows - 1) * out_row_bytes + 32 * C::NVA * 2 : 0, 0x00020000);
+        const int out_voff = 4 * g2 * out_row_bytes + 2 * l32;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int db = 0; db < C::NVA; ++db)
+          for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float val = acc[db][kb][i] * p.scale;
-            if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
-            else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
-          }
+            for (int i = 0; i < 16; ++i) {
+              const __bf16 val = (__bf16)(acc[db][kb][i] * p.scale);
+              __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rout, out_voff,
+                                                    (32 * kb + 8 * (i / 4) + (i % 4)) * out_row_bytes + 64 * db, 0);
+            }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const float val = acc[db][kb][i] * p.scale;
+              if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
+              else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
+            }
+      }
     }
     pt.mark(3);
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
@@ -411,10 +432,12 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
                     const float* delta, const int32_t* cu_seqlens_kv, int32_t n_seqs,
                     const fcp_work_desc* work, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq,
                     int32_t hkv, int32_t head_dim, float softmax_scale, const int32_t* q_limit, const int32_t* k_from,
-                    float* dq_acc, float* dk_acc, float* dv_acc, void* scratch, size_t scratch_bytes, void* stream) {
+                    float* dq_acc, float* dk_acc, float* dv_acc, void* scratch, size_t scratch_bytes, void* stream,
+                    void* dq_out = nullptr, void* dk_out = nullptr, void* dv_out = nullptr) {
   fcp::clear_error();
   if (!q || !k || !v || !d_o || !lse || !delta || !cu_seqlens_kv || !dq_acc || !dk_acc || !dv_acc || !scratch)
     return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: null pointer");
+  const bool direct = dq_out != nullptr;
   if (n_work > 0 && !work) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: work is NULL");
   if (tq < 0 || tkv < 1 || n_seqs < 1 || n_work < 0 || hq < 1 || hkv < 1)
     return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step: bad sizes");
@@ -440,6 +463,13 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
   float* stats = reinterpret_cast<float*>(static_cast<char*>(region_q) + fcp::sched_region_bytes(n_work, cap_q));
+  if (direct) {   // where every row's result comes from; clears the accumulator rows that are accumulated into
+    const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs,
+                                           tq, tkv, fcp::bwd_q_state(scratch, n_work, tq, tkv, hq),
+                                           fcp::bwd_kv_state(scratch, n_work, tq, tkv, hq), dq_acc, dk_acc, dv_acc,
+                                           hq * head_dim, hkv * head_dim, st);
+    if (rcs != FCP_OK) return rcs;
+  }
   if (tq == 0 || n_work == 0) {     // nothing to add; the lists are still built so that the status call works
     int rc0 = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
     if (rc0 != FCP_OK) return rc0;
@@ -454,6 +484,7 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   p.lse = lse; p.delta = delta; p.stats = stats;
   p.q_limit = q_limit; p.k_from = k_from;
   p.dq = dq_acc; p.dk = dk_acc; p.dv = dv_acc;
+  p.dq_out = (uint16_t*)dq_out; p.dk_out = (uint16_t*)dk_out; p.dv_out = (uint16_t*)dv_out;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.scale = softmax_scale; p.scale_log2 = softmax_scale * fcp::kLog2e;
 
@@ -509,4 +540,21 @@ extern "C" int fcp_attn_bwd_step_mixed(const void* q, const void* k, const void*
   }
   return bwd_step(q, k, v, d_o, lse, delta, cu_seqlens_kv, n_seqs, work, n_work, tq, tkv, hq, hkv, head_dim,
                   softmax_scale, q_limit, k_from, dq_acc, dk_acc, dv_acc, scratch, scratch_bytes, stream);
+}
+
+extern "C" int fcp_attn_bwd_step_direct(const void* q, const void* k, const void* v, const void* d_o, const float* lse,
+                                        const float* delta, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                                        const fcp_work_desc* work, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq,
+                                        int32_t hkv, int32_t head_dim, float softmax_scale, const int32_t* q_limit,
+                                        const int32_t* k_from, float* dq_acc, float* dk_acc, float* dv_acc, void* dq_out,
+                                        void* dk_out, void* dv_out, void* scratch, size_t scratch_bytes, void* stream) {
+  fcp::clear_error();
+  if (!dq_out || !dk_out || !dv_out) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step_direct: output pointer is NULL");
+  if ((q_limit == nullptr) != (k_from == nullptr))
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step_direct: q_limit and k_from go together");
+  if ((reinterpret_cast<uintptr_t>(dq_out) | reinterpret_cast<uintptr_t>(dk_out) | reinterpret_cast<uintptr_t>(dv_out)) & 15u)
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_bwd_step_direct: outputs must be 16-byte aligned");
+  return bwd_step(q, k, v, d_o, lse, delta, cu_seqlens_kv, n_seqs, work, n_work, tq, tkv, hq, hkv, head_dim,
+                  softmax_scale, q_limit, k_from, dq_acc, dk_acc, dv_acc, scratch, scratch_bytes, stream, dq_out, dk_out,
+                  dv_out);
 }

@@ -347,12 +347,14 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           n_pair_keys > 0 ? (n_pair_keys - 1) * row_bytes + 32 * C::NVA * 4 : 0, 0x00020000);
       const int acc_voff = 4 * g2 * row_bytes + 4 * l32;
       auto acc_soff = [&](int kb, int db, int i) { return (32 * kb + 8 * (i / 4) + (i % 4)) * row_bytes + 128 * db; };
+      // Direct mode: the unit owns its keys, so nothing is read and the epilogue writes the final bf16 rows.
+      const bool direct = exclusive && p.dk_out != nullptr;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int db = 0; db < C::NVA; ++db) {
           acc[db][kb] = zero16();
-          if (exclusive) {
+          if (exclusive && !direct) {
 #pragma unroll
             for (int i = 0; i < 16; ++i)
               acc[db][kb][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(racc, acc_voff, acc_soff(kb, db, i), 0));
@@ -360,7 +362,7 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         }
       // (explicit wait: the compiler must not be left to wait for these loads inside the step loop)
       __builtin_amdgcn_s_waitcnt(0x0F70);
-      if (exclusive && role != 1) {
+      if (exclusive && !direct && role != 1) {
         const float inv = 1.f / p.scale;
 #pragma unroll
         for (int db = 0; db < C::NVA; ++db)
@@ -439,17 +441,36 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
         }
         pt.mark(3);
       }
-      // epilogue: dV or dK [key x channel] -> pool accumulators
+      // epilogue: dV or dK [key x channel] -> pool accumulators (or, in direct mode, the final bf16 rows: half a line
+      // per store)
+      if (direct) {
+        const int out_row_bytes = p.hkv * D * 2;
+        const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)((role == 1 ? p.dv_out : p.dk_out) + ((kv_row0 + 64 * kp) * p.hkv + kvh) * D + 32 * C::NVA * ch), (short)0,
+            n_pair_keys > 0 ? (n_pair_keys - 1) * out_row_bytes + 32 * C::NVA * 2 : 0, 0x00020000);
+        const int out_voff = 4 * g2 * out_row_bytes + 2 * l32;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int db = 0; db < C::NVA; ++db)
+          for (int db = 0; db < C::NVA; ++db)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const float val = acc[db][kb][i] * mul;
-            if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
-            else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
-          }
+            for (int i = 0; i < 16; ++i) {
+              const __bf16 val = (__bf16)(acc[db][kb][i] * mul);
+              __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rout, out_voff,
+                                                    (32 * kb + 8 * (i / 4) + (i % 4)) * out_row_bytes + 64 * db, 0);
+            }
+      } else {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int db = 0; db < C::NVA; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+              const float val = acc[db][kb][i] * mul;
+              if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
+              else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
+            }
+      }
     }
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }

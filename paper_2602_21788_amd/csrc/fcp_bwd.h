@@ -19,6 +19,11 @@ struct BwdParams {
   float* dq;
   float* dk;
   float* dv;
+  // Direct mode (all three set, or all NULL): a unit that owns its rows / keys in this launch (the scheduler's
+  // exclusivity flags) writes its final bf16 result here and leaves the fp32 accumulator alone.
+  uint16_t* dq_out;
+  uint16_t* dk_out;
+  uint16_t* dv_out;
   int32_t tq, hq, hkv;
   float scale, scale_log2;
 };

@@ -134,4 +134,20 @@ int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int3
                         int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
                         const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream);
 
+// Direct mode of the backward: one state byte per query row and per pool key (0 untouched, 1 accumulated in fp32 -
+// the accumulator row is cleared here -, 2 written directly as bf16 by the unit that owns it).
+int launch_row_states(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from, const fcp_work_desc* work,
+                      int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
+                      uint8_t* q_state, uint8_t* kv_state, float* dq_acc, float* dk_acc, float* dv_acc,
+                      int32_t q_row_elems, int32_t kv_row_elems, hipStream_t stream);
+
+// Where the row states live in the backward's scratch buffer (after the two lists and the statistics planes).
+inline uint8_t* bwd_q_state(void* scratch, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq) {
+  return static_cast<uint8_t*>(scratch) + sched_region_bytes(n_work, kv_tile_cap(tkv, n_work)) +
+         sched_region_bytes(n_work, q_tile_cap(tq, tkv, n_work, 1 << 20)) + pad_to((size_t)hq * (size_t)tq * 8, 256);
+}
+inline uint8_t* bwd_kv_state(void* scratch, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq) {
+  return bwd_q_state(scratch, n_work, tq, tkv, hq) + pad_to((size_t)tq, 256);
+}
+
 }  // namespace fcp

@@ -111,6 +111,43 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
   }
 }
 
+// Direct mode of the backward: the rows whose results were accumulated in fp32 (state 1) are converted, rows that
+// no unit touched (state 0) are zero, rows written directly by their unit (state 2) are left alone.  One wave per
+// row of dQ [tq], then dK [tkv], then dV [tkv].
+__global__ __launch_bounds__(256) void finalize_direct_kernel(
+    const uint8_t* __restrict__ q_state, const uint8_t* __restrict__ kv_state, int32_t tq, int32_t tkv,
+    int32_t q_row_elems, int32_t kv_row_elems, const float* __restrict__ dq_acc, const float* __restrict__ dk_acc,
+    const float* __restrict__ dv_acc, uint32_t* __restrict__ dq_out, uint32_t* __restrict__ dk_out,
+    uint32_t* __restrict__ dv_out) {
+  const int lane = threadIdx.x & 63;
+  const int64_t n_rows = (int64_t)tq + 2 * (int64_t)tkv;
+  const int64_t wstride = (int64_t)gridDim.x * 4;
+  for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < n_rows; r += wstride) {
+    int state, elems;
+    const float* src;
+    uint32_t* dst;
+    if (r < tq) {
+      state = q_state[r]; elems = q_row_elems;
+      src = dq_acc + r * q_row_elems; dst = dq_out + r * (q_row_elems / 2);
+    } else {
+      const bool is_v = r >= (int64_t)tq + tkv;
+      const int64_t kr = r - tq - (is_v ? tkv : 0);
+      state = kv_state[kr]; elems = kv_row_elems;
+      src = (is_v ? dv_acc : dk_acc) + kr * kv_row_elems; dst = (is_v ? dv_out : dk_out) + kr * (kv_row_elems / 2);
+    }
+    if (state == 2) continue;
+    for (int32_t e = lane; e < elems / 8; e += 64) {
+      u32x4 o = {0u, 0u, 0u, 0u};
+      if (state == 1) {
+        const f32x4* s4 = reinterpret_cast<const f32x4*>(src) + 2 * e;
+        const f32x4 x0 = s4[0], x1 = s4[1];
+        o = u32x4{pack_bf16(x0[0], x0[1]), pack_bf16(x0[2], x0[3]), pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+      }
+      reinterpret_cast<u32x4*>(dst)[e] = o;
+    }
+  }
+}
+
 }  // namespace
 }  // namespace fcp
 
@@ -172,6 +209,26 @@ extern "C" int fcp_grad_finalize(const float* acc, void* out_bf16, int64_t n, vo
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(fcp::finalize_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, acc,
                      (uint32_t*)out_bf16, n8, n);
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}
+
+extern "C" int fcp_grad_finalize_direct(const float* dq_acc, const float* dk_acc, const float* dv_acc, void* dq_out,
+                                        void* dk_out, void* dv_out, void* scratch, int64_t n_work, int32_t tq,
+                                        int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim, void* stream) {
+  fcp::clear_error();
+  if (!dq_acc || !dk_acc || !dv_acc || !dq_out || !dk_out || !dv_out || !scratch)
+    return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize_direct: null pointer");
+  if (tq < 0 || tkv < 1 || hq < 1 || hkv < 1 || n_work < 0) return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize_direct: bad sizes");
+  if (head_dim != 64 && head_dim != 128) return fail(FCP_ERR_UNSUPPORTED, "fcp_grad_finalize_direct: head_dim %d not 64/128", head_dim);
+  if (!aligned16(dq_acc) || !aligned16(dk_acc) || !aligned16(dv_acc) || !aligned16(dq_out) || !aligned16(dk_out) || !aligned16(dv_out))
+    return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize_direct: pointers must be 16-byte aligned");
+  int64_t blocks = ((int64_t)tq + 2 * (int64_t)tkv + 3) / 4;
+  if (blocks > 16384) blocks = 16384;
+  hipLaunchKernelGGL(fcp::finalize_direct_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                     fcp::bwd_q_state(scratch, n_work, tq, tkv, hq), fcp::bwd_kv_state(scratch, n_work, tq, tkv, hq), tq, tkv,
+                     hq * head_dim, hkv * head_dim, dq_acc, dk_acc, dv_acc, (uint32_t*)dq_out, (uint32_t*)dk_out,
+                     (uint32_t*)dv_out);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
 }

@@ -126,6 +126,38 @@ __device__ inline int32_t block_exclusive_scan(int32_t v, int32_t* s_wave, int32
   return base + inc - v;
 }
 
+// Exclusivity flags: an item whose query rows (key segments) no other valid item of this launch touches lets the
+// backward kernels add to dQ (dK/dV) without atomics, or write the final result directly.  The items' ranges are
+// staged in LDS (seq, -1 = invalid; q range; two key ranges) so that the all-pairs scan does not wait on global memory.
+__device__ inline void stage_item(int32_t (&r)[7], const fcp_work_desc& a, bool ok) {
+  r[0] = ok ? a.seq : -1;
+  r[1] = a.q_local_off;
+  r[2] = a.q_local_off + a.q_len;
+  r[3] = a.k_seq_start[0];
+  r[4] = a.k_seq_start[0] + a.k_len[0];
+  r[5] = a.n_seg > 1 ? a.k_seq_start[1] : 0;
+  r[6] = a.n_seg > 1 ? a.k_seq_start[1] + a.k_len[1] : 0;   // empty range when absent
+}
+__device__ inline int32_t exclusive_flags(const int32_t (*rng)[7], int32_t i, int32_t n_work) {
+  if (rng[i][0] < 0) return 0;
+  int32_t flags = kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive;
+  const int32_t seq = rng[i][0], q0 = rng[i][1], q1 = rng[i][2];
+  const int32_t k0[2] = {rng[i][3], rng[i][5]}, k1[2] = {rng[i][4], rng[i][6]};
+  if (k0[0] < k1[1] && k0[1] < k1[0]) flags &= kFlagQExclusive;   // own segments overlap
+  for (int32_t j = 0; j < n_work; ++j) {
+    if (j == i || rng[j][0] < 0) continue;
+    if (q0 < rng[j][2] && rng[j][1] < q1) flags &= ~kFlagQExclusive;
+    if (rng[j][0] == seq) {
+#pragma unroll
+      for (int sa = 0; sa < 2; ++sa) {
+        if ((k0[sa] < rng[j][4] && rng[j][3] < k1[sa]) || (k0[sa] < rng[j][6] && rng[j][5] < k1[sa]))
+          flags &= ~(sa == 0 ? kFlagSeg0Exclusive : kFlagSeg1Exclusive);
+      }
+    }
+  }
+  return flags;
+}
+
 // One tile list, built by one block.
 __device__ void build_list(
     int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
@@ -160,43 +192,13 @@ __device__ void build_list(
     if (tid == 0) s_carry = carry + total;
     __syncthreads();
   }
-  // Exclusivity flags: an item whose query rows (key segments) no other valid item of this
-  // launch touches lets the backward kernels add to dQ (dK/dV) without atomics.  The items'
-  // ranges are staged in LDS so that the all-pairs scan does not wait on global memory.
   if (n_work <= kMaxExclusiveScan) {
     for (int32_t i = tid; i < n_work; i += kSchedThreads) {
       const fcp_work_desc a = work[i];
-      const bool ok = item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys);
-      s_rng[i][0] = ok ? a.seq : -1;
-      s_rng[i][1] = a.q_local_off;
-      s_rng[i][2] = a.q_local_off + a.q_len;
-      s_rng[i][3] = a.k_seq_start[0];
-      s_rng[i][4] = a.k_seq_start[0] + a.k_len[0];
-      s_rng[i][5] = a.n_seg > 1 ? a.k_seq_start[1] : 0;
-      s_rng[i][6] = a.n_seg > 1 ? a.k_seq_start[1] + a.k_len[1] : 0;   // empty range when absent
+      stage_item(s_rng[i], a, item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys));
     }
     __syncthreads();
-    for (int32_t i = tid; i < n_work; i += kSchedThreads) {
-      int32_t flags = 0;
-      if (s_rng[i][0] >= 0) {
-        flags = kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive;
-        const int32_t seq = s_rng[i][0], q0 = s_rng[i][1], q1 = s_rng[i][2];
-        const int32_t k0[2] = {s_rng[i][3], s_rng[i][5]}, k1[2] = {s_rng[i][4], s_rng[i][6]};
-        if (k0[0] < k1[1] && k0[1] < k1[0]) flags &= kFlagQExclusive;   // own segments overlap
-        for (int32_t j = 0; j < n_work; ++j) {
-          if (j == i || s_rng[j][0] < 0) continue;
-          if (q0 < s_rng[j][2] && s_rng[j][1] < q1) flags &= ~kFlagQExclusive;
-          if (s_rng[j][0] == seq) {
-#pragma unroll
-            for (int sa = 0; sa < 2; ++sa) {
-              if ((k0[sa] < s_rng[j][4] && s_rng[j][3] < k1[sa]) || (k0[sa] < s_rng[j][6] && s_rng[j][5] < k1[sa]))
-                flags &= ~(sa == 0 ? kFlagSeg0Exclusive : kFlagSeg1Exclusive);
-            }
-          }
-        }
-      }
-      item_flags[i] = flags;
-    }
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = exclusive_flags(s_rng, i, n_work);
   } else {
     for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = 0;
   }
@@ -338,7 +340,97 @@ __global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
              j.tile_cap, j.hdr, j.item_off, j.item_flags, j.tiles);
 }
 
+// Direct mode of the backward: where does the result of every query row / pool key come from?  State 0: no unit of
+// this launch touches it (the result is zero); 1: it is accumulated in fp32 (several units, atomics) and converted
+// afterwards - its accumulator row is cleared here; 2: one unit owns it and writes the final bf16 row itself.  The
+// states follow the same exclusivity flags the kernels act on.  One wave per row.
+__global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
+    int32_t max_seg_keys, const MaskTables m, const fcp_work_desc* __restrict__ work, int32_t n_work,
+    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, uint8_t* __restrict__ q_state,
+    uint8_t* __restrict__ kv_state, float* __restrict__ dq_acc, float* __restrict__ dk_acc, float* __restrict__ dv_acc,
+    int32_t q_row_elems, int32_t kv_row_elems) {
+  __shared__ int32_t s_rng[kMaxExclusiveScan][7];
+  __shared__ int32_t s_vis[kMaxExclusiveScan][2];   // keys of each segment that the item's last row sees
+  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int32_t i = tid; i < n_work; i += kSchedThreads) {
+    const fcp_work_desc a = work[i];
+    const bool ok = item_valid(a, cu, n_seqs, tq, tkv, 1, false, max_seg_keys);
+    stage_item(s_rng[i], a, ok);
+    s_vis[i][0] = ok ? visible_len(m, a, 0, a.q_len - 1) : 0;
+    s_vis[i][1] = ok && a.n_seg > 1 ? visible_len(m, a, 1, a.q_len - 1) : 0;
+  }
+  __syncthreads();
+  for (int32_t i = tid; i < n_work; i += kSchedThreads) s_fl[i] = (uint8_t)exclusive_flags(s_rng, i, n_work);
+  __syncthreads();
+
+  const int64_t n_rows = (int64_t)tq + tkv;
+  const int64_t wave0 = (int64_t)blockIdx.x * (kSchedThreads / 64) + (tid >> 6);
+  const int64_t wstride = (int64_t)gridDim.x * (kSchedThreads / 64);
+  const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int64_t r = wave0; r < n_rows; r += wstride) {
+    int32_t cnt = 0, own = 0;            // covering (item, segment) pairs among this lane's items; flags bit of the last
+    if (r < tq) {
+      for (int32_t j = lane; j < n_work; j += 64)
+        if (s_rng[j][0] >= 0 && s_rng[j][1] <= r && r < s_rng[j][2]) { ++cnt; own = s_fl[j] & kFlagQExclusive; }
+    } else {
+      const int32_t kr = (int32_t)(r - tq);
+      int32_t lo = 0, hi = n_seqs;       // sequence of the pool row: last seq with cu[seq] <= kr
+      while (lo < hi) {
+        const int32_t mid = (lo + hi + 1) >> 1;
+        if (cu[mid] <= kr) lo = mid; else hi = mid - 1;
+      }
+      if (lo < n_seqs && kr < cu[lo + 1]) {
+        const int32_t pos = kr - cu[lo];
+        for (int32_t j = lane; j < n_work; j += 64) {
+          if (s_rng[j][0] != lo) continue;
+          if (s_rng[j][3] <= pos && pos < s_rng[j][3] + s_vis[j][0]) { ++cnt; own = s_fl[j] & kFlagSeg0Exclusive; }
+          if (s_rng[j][5] <= pos && pos < s_rng[j][5] + s_vis[j][1]) { ++cnt; own = s_fl[j] & kFlagSeg1Exclusive; }
+        }
+      }
+    }
+    int32_t total = cnt, any_own = own;
+    for (int off = 32; off > 0; off >>= 1) {
+      total += __shfl_xor(total, off, 64);
+      any_own |= __shfl_xor(any_own, off, 64);
+    }
+    const int state = total == 0 ? 0 : (total == 1 && any_own != 0) ? 2 : 1;
+    if (r < tq) {
+      if (lane == 0) q_state[r] = (uint8_t)state;
+      if (state == 1) {
+        float4* row = reinterpret_cast<float4*>(dq_acc + r * q_row_elems);
+        for (int32_t e = lane; e < q_row_elems / 4; e += 64) row[e] = zero;
+      }
+    } else {
+      const int64_t kr = r - tq;
+      if (lane == 0) kv_state[kr] = (uint8_t)state;
+      if (state == 1) {
+        float4* rk = reinterpret_cast<float4*>(dk_acc + kr * kv_row_elems);
+        float4* rv = reinterpret_cast<float4*>(dv_acc + kr * kv_row_elems);
+        for (int32_t e = lane; e < kv_row_elems / 4; e += 64) { rk[e] = zero; rv[e] = zero; }
+      }
+    }
+  }
+}
+
 }  // namespace
+
+int launch_row_states(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from, const fcp_work_desc* work,
+                      int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
+                      uint8_t* q_state, uint8_t* kv_state, float* dq_acc, float* dk_acc, float* dv_acc,
+                      int32_t q_row_elems, int32_t kv_row_elems, hipStream_t stream) {
+  if (n_work > kMaxExclusiveScan)
+    return fail(FCP_ERR_UNSUPPORTED, "direct backward: more than %d work items (use the accumulating entry point)", kMaxExclusiveScan);
+  int64_t blocks = ((int64_t)tq + tkv + kSchedThreads / 64 - 1) / (kSchedThreads / 64);
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(row_state_kernel, dim3((unsigned)blocks), dim3(kSchedThreads), 0, stream,
+                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work,
+                     (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, q_state, kv_state, dq_acc, dk_acc, dv_acc,
+                     q_row_elems, kv_row_elems);
+  FCP_HIP_CHECK(hipGetLastError());
+  return FCP_OK;
+}
 
 int64_t q_tile_cap(int32_t tq, int32_t tkv, int64_t n_work, int32_t n_parts) {
   const int64_t by_slots = (int64_t)n_parts * ((tq + kMinQTile - 1) / kMinQTile);
@@ -405,10 +497,12 @@ extern "C" size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t 
                                     int32_t head_dim, int64_t n_work, int32_t n_parts) {
   (void)hkv; (void)head_dim;
   if (tq < 0 || tkv < 0 || n_work < 0 || n_parts < 0) return 0;
-  if (which == FCP_SCRATCH_BWD)   // key-tile list (dK/dV kernel), query-tile list (dQ kernel), packed row statistics
+  if (which == FCP_SCRATCH_BWD)   // key-tile list (dK/dV kernel), query-tile list (dQ kernel), packed row statistics,
+                                  // row states
     return fcp::sched_region_bytes(n_work, fcp::kv_tile_cap(tkv, n_work)) +
            fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, 1 << 20)) +
-           fcp::pad_to((size_t)hq * (size_t)tq * 8, 256);
+           fcp::pad_to((size_t)hq * (size_t)tq * 8, 256) +
+           fcp::pad_to((size_t)tq, 256) + fcp::pad_to((size_t)tkv, 256);   // + row states of the direct mode
   return fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, n_parts));
 }
 

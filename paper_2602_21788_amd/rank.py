@@ -156,6 +156,23 @@ class RankAttention:
         self.backward_steps(stream)
         self.finalize(stream)
 
+    # The same results without clearing and converting every accumulator row: rows owned by one unit of work are
+    # written as bf16 by the kernel that computes them (fcp_attn_bwd_step_direct + fcp_grad_finalize_direct).
+    def backward_steps_direct(self, stream=None):
+        B.fcp_attn_bwd_step_direct(self.q, self.k, self.v, self.d_o, self.lse, self.delta, self.cu_d, self.work_d,
+                                   self.scale, self.dq_acc, self.dk_acc, self.dv_acc, self.dq, self.dk, self.dv,
+                                   self.scratch_b, q_limit=self.q_limit_d if self.spans is not None else None,
+                                   k_from=self.k_from_d if self.spans is not None else None, stream=stream)
+
+    def finalize_direct(self, stream=None):
+        B.fcp_grad_finalize_direct(self.dq_acc, self.dk_acc, self.dv_acc, self.dq, self.dk, self.dv, self.scratch_b,
+                                   self.n_work, stream)
+
+    def backward_direct(self, stream=None):
+        self.backward_delta(stream)
+        self.backward_steps_direct(stream)
+        self.finalize_direct(stream)
+
     # -- bookkeeping ------------------------------------------------------------------
     def pairs(self) -> int:
         """Visible (query, key) pairs of this rank: sum over its rows of (position + 1), or of

@@ -77,4 +77,19 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
             assert res[name] <= TOL_BF16_REL, (label, name, res)
         res["_dK_acc"] = ra.dk_acc.cpu().numpy().astype(np.float64)
         res["_dV_acc"] = ra.dv_acc.cpu().numpy().astype(np.float64)
+        # The direct backward (rows owned by one unit written as bf16 by their kernel) on poisoned buffers: it must
+        # neither need cleared accumulators nor leave any output row unwritten, and meets the same bar.
+        for t in (ra.dq_acc, ra.dk_acc, ra.dv_acc, ra.dq, ra.dk, ra.dv):
+            t.fill_(float("nan"))
+        ra.backward_direct()
+        torch.cuda.synchronize()
+        n_tiles, n_rej = __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_b)
+        assert n_rej == 0, f"{label}: {n_rej} work items rejected (direct bwd)"
+        direct = {"dQ": bf16_tensor_to_f64(ra.dq), "dK": bf16_tensor_to_f64(ra.dk), "dV": bf16_tensor_to_f64(ra.dv)}
+        for name, ref in (("dQ", dQ_ref), ("dK", dK_ref), ("dV", dV_ref)):
+            assert np.isfinite(direct[name]).all(), (label, name, "direct")
+            res[name + "_direct"] = rel_err(direct[name], ref)
+            assert res[name + "_direct"] <= TOL_BF16_REL, (label, name, "direct", res)
+            # against the accumulating path: the same arithmetic, except for the order of the fp32 atomics
+            assert rel_err(direct[name], got[name]) <= 2.0 ** -7, (label, name, "direct vs accumulating")
     return res

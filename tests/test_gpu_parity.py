@@ -104,6 +104,16 @@ def test_cfg2_full_size_sampled():
     dQ, dK, dV = (bf16_tensor_to_f64(x) for x in (ra.dq, ra.dk, ra.dv))
     for x in (O, LSE, dQ, dK, dV):
         assert np.isfinite(x).all()
+    # The direct backward (what bench.py times) on poisoned buffers: every element against the accumulating path,
+    # which is checked against the oracle below - the arithmetic is the same up to the order of the fp32 atomics.
+    for t in (ra.dq_acc, ra.dk_acc, ra.dv_acc, ra.dq, ra.dk, ra.dv):
+        t.fill_(float("nan"))
+    ra.backward_direct()
+    torch.cuda.synchronize()
+    for name, acc, x in (("dQ", dQ, ra.dq), ("dK", dK, ra.dk), ("dV", dV, ra.dv)):
+        d = bf16_tensor_to_f64(x)
+        assert np.isfinite(d).all(), name
+        assert rel_err(d, acc) <= 2.0 ** -7, (name, "direct vs accumulating", rel_err(d, acc))
     G = wl.hq // wl.hkv
     sel = np.arange(0, len(rows), 61)
     for kvh in (0, 5):
