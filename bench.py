@@ -2,9 +2,10 @@
 """Benchmark of the FCP rank-local attention hot path on one MI355X.
 
 A "step" is one pass of the whole path for the reported rank of the workload:
-  fcp_attn_fwd_step (all ring steps) -> fcp_lse_merge -> fcp_attn_bwd_delta ->
+  fcp_attn_fwd_step_direct (all ring steps) -> fcp_lse_merge_direct -> fcp_attn_bwd_delta ->
   fcp_attn_bwd_step_direct (all ring steps) -> fcp_grad_finalize_direct
-(--backward accumulate: ... -> zero grads -> fcp_attn_bwd_delta -> fcp_attn_bwd_step -> fcp_grad_finalize x3),
+(--forward partial: fcp_attn_fwd_step -> fcp_lse_merge;  --backward accumulate: zero grads -> fcp_attn_bwd_delta ->
+fcp_attn_bwd_step -> fcp_grad_finalize x3),
 with every input already resident in HBM.  The metric is causal-effective TFLOP/s:
 14 * pairs * head_dim * hq / time (4 forward + 10 backward flops per visible pair, channel
 and head; masked pairs are not counted).  --mask mixed times the same path through the
@@ -106,10 +107,11 @@ def main():
     ap.add_argument("--mask", choices=["causal", "mixed"], default="causal",
                     help="mixed: the same workload with synthetic image spans (576 tokens each, about 35 %% of a "
                          "sequence) that attend in full; pairs and flops then count the pairs visible under that mask")
-    ap.add_argument("--forward", choices=["partial", "running"], default="partial",
-                    help="running: the forward pass as one fcp_attn_fwd_step_running call per ring step (no partial "
-                         "results, no fcp_lse_merge) instead of fcp_attn_fwd_step + fcp_lse_merge; a comparison, not "
-                         "the headline path")
+    ap.add_argument("--forward", choices=["direct", "partial", "running"], default="direct",
+                    help="direct (default): fcp_attn_fwd_step_direct + fcp_lse_merge_direct - rows fed by one work item "
+                         "get their final O / LSE from the forward kernel, only the others are merged; partial: "
+                         "fcp_attn_fwd_step + fcp_lse_merge for every row; running: one fcp_attn_fwd_step_running call "
+                         "per ring step (no partial results, no merge), a comparison")
     ap.add_argument("--backward", choices=["direct", "accumulate"], default="direct",
                     help="direct (default): fcp_attn_bwd_step_direct + fcp_grad_finalize_direct - rows whose whole "
                          "gradient comes from one unit of work are written as bf16 by their kernel, nothing is cleared "
@@ -157,6 +159,9 @@ def main():
         if args.forward == "running":
             mark(0); ra.forward_running()
             mark(1)
+        elif args.forward == "direct":
+            mark(0); ra.forward_steps_direct()
+            mark(1); ra.merge_direct()
         else:
             mark(0); ra.forward_steps()
             mark(1); ra.merge()
@@ -192,7 +197,7 @@ def main():
     value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
     bwd_tflops = flops_bwd / (seg_ms["bwd_step"] * 1e-3) / 1e12
     fwd_tflops = flops_fwd / (seg_ms["fwd_step"] * 1e-3) / 1e12
-    merge_gbs = ra.merge_bytes() / (seg_ms["merge"] * 1e-3) / 1e9
+    merge_gbs = ra.merge_bytes(direct=args.forward == "direct") / (seg_ms["merge"] * 1e-3) / 1e9
     out = {
         "metric": "rank-local varlen causal attn TFLOP/s fwd+bwd, % of MFMA bf16 peak",
         "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,

@@ -127,6 +127,28 @@ int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t
 int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
                   int32_t hq, int32_t head_dim, void* o, float* lse, void* stream);
 
+/*
+ * fcp_attn_fwd_step_direct / fcp_lse_merge_direct -- the whole forward of a rank with final results written once.
+ * Same function as fcp_attn_fwd_step (+ _mixed when q_limit is given) followed by fcp_lse_merge, for a work list that
+ * carries ALL ring steps.  Rows that get all their keys from one work item (every sequence that is not sharded,
+ * paper Sec. 4.1; no other item of the call covers the item's query rows) need no partial result and no merge
+ * (Sec. 3.2: the rescaling combines the steps of a ring): the kernel writes their normalised O as bf16 into o and
+ * their LSE into lse.  The other rows get partial results in o_part / lse_part as in fcp_attn_fwd_step;
+ * fcp_lse_merge_direct merges those, gives rows that no item covers O = 0 and LSE = -inf, and leaves the directly
+ * written rows alone.  The row states stay in `scratch` between the two calls.
+ *   o [tq,hq,D] bf16, lse [hq,tq] fp32: device, complete after fcp_lse_merge_direct;  o_part / lse_part: defined only
+ *   for the rows that are merged.  n_work <= 1024 (FCP_ERR_UNSUPPORTED beyond).  Other arguments, alignment and errors
+ *   as in fcp_attn_fwd_step; fcp_lse_merge_direct takes the same n_parts, tq, tkv, n_work and scratch.
+ */
+int fcp_attn_fwd_step_direct(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                             int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                             int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                             float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part,
+                             void* o, float* lse, void* scratch, size_t scratch_bytes, void* stream);
+int fcp_lse_merge_direct(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
+                         int32_t tkv, int32_t hq, int32_t head_dim, void* o, float* lse, void* scratch,
+                         int64_t n_work, void* stream);
+
 /* Backward prologue: delta[h, i] = sum_c dO[i,h,c] * O[i,h,c]  (fp32).  Device pointers. */
 int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, int32_t head_dim,
                        float* delta, void* stream);

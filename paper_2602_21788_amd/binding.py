@@ -28,7 +28,7 @@ SPAN_DTYPE = np.dtype([("seq", "<i4"), ("start", "<i4"), ("len", "<i4")])
 EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_plan_groups", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
            "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status",
            "fcp_group_shard_args", "fcp_attn_fwd_step_running", "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed",
-           "fcp_attn_bwd_step_direct", "fcp_grad_finalize_direct"]
+           "fcp_attn_bwd_step_direct", "fcp_grad_finalize_direct", "fcp_attn_fwd_step_direct", "fcp_lse_merge_direct"]
 
 
 class FcpError(RuntimeError):
@@ -87,6 +87,10 @@ def lib() -> ctypes.CDLL:
                                                P, P, P, SZ, P]
         L.fcp_grad_finalize_direct.restype = ctypes.c_int
         L.fcp_grad_finalize_direct.argtypes = [P, P, P, P, P, P, P, I64, I32, I32, I32, I32, I32, P]
+        L.fcp_attn_fwd_step_direct.restype = ctypes.c_int
+        L.fcp_attn_fwd_step_direct.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, I32, F, P, P, P, P, P, P, SZ, P]
+        L.fcp_lse_merge_direct.restype = ctypes.c_int
+        L.fcp_lse_merge_direct.argtypes = [P, P, I32, I32, I32, I32, I32, P, P, P, I64, P]
         _lib = L
     return _lib
 
@@ -306,6 +310,26 @@ def fcp_attn_bwd_step_mixed(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softm
                                          _dev_ptr(q_limit), _dev_ptr(k_from), _dev_ptr(dq_acc), _dev_ptr(dk_acc),
                                          _dev_ptr(dv_acc), _dev_ptr(scratch), scratch.numel() * scratch.element_size(),
                                          _stream(stream)))
+
+
+def fcp_attn_fwd_step_direct(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, o_part, lse_part, o, lse, scratch,
+                             q_limit=None, stream=None):
+    """Whole forward of a rank: rows fed by one work item get their final O / LSE at once (see include/fcp.h)."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_fwd_step_direct(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(cu_seqlens_kv),
+                                          cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, int(n_parts), tq, tkv, hq, hkv,
+                                          D, float(softmax_scale), _dev_ptr(q_limit), _dev_ptr(o_part), _dev_ptr(lse_part),
+                                          _dev_ptr(o), _dev_ptr(lse), _dev_ptr(scratch),
+                                          scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_lse_merge_direct(o_part, lse_part, o, lse, tkv, scratch, n_work, stream=None):
+    """Second half of the direct forward: merges the rows that have partial results."""
+    n_parts, tq, hq, D = o_part.shape
+    _check(lib().fcp_lse_merge_direct(_dev_ptr(o_part), _dev_ptr(lse_part), n_parts, tq, int(tkv), hq, D, _dev_ptr(o),
+                                      _dev_ptr(lse), _dev_ptr(scratch), int(n_work), _stream(stream)))
 
 
 def fcp_attn_bwd_step_direct(q, k, v, d_o, lse, delta, cu_seqlens_kv, work, softmax_scale, dq_acc, dk_acc, dv_acc,

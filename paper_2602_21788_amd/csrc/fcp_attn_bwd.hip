@@ -464,7 +464,7 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
   float* stats = reinterpret_cast<float*>(static_cast<char*>(region_q) + fcp::sched_region_bytes(n_work, cap_q));
   if (direct) {   // where every row's result comes from; clears the accumulator rows that are accumulated into
-    const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs,
+    const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, 1, false, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs,
                                            tq, tkv, fcp::bwd_q_state(scratch, n_work, tq, tkv, hq),
                                            fcp::bwd_kv_state(scratch, n_work, tq, tkv, hq), dq_acc, dk_acc, dv_acc,
                                            hq * head_dim, hkv * head_dim, st);

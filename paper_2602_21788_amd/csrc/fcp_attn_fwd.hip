@@ -45,8 +45,10 @@ struct FwdParams {
   float* o_part;
   float* lse_part;
   const int32_t* q_limit;   // [tq] last key position each local query row sees, NULL = its own position (causal)
-  uint16_t* o_out;          // running mode only: merged O as bf16 [tq,hq,D], or NULL
+  uint16_t* o_out;          // running and direct mode: final O as bf16 [tq,hq,D], or NULL
+  float* lse_out;           // direct mode: final LSE [hq,tq]
   int32_t running;          // 1: slot 0 of o_part / lse_part is the caller's running result, continued and rewritten
+  int32_t direct;           // 1: a tile whose rows no other item of the launch covers writes o_out / lse_out, no partial
   int32_t tq, hq, hkv;
   int32_t head_pair;  // 1: a unit is a 128-row tile for TWO heads of one KV head; 0: a 256-row tile for one head
   float scale_log2;   // softmax_scale * log2(e)
@@ -421,7 +423,9 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     const float l_tot = lane32_partner_sum(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     scale_rows(inv);
-    {
+    // Direct mode: the tile's rows get all their keys in this unit, so the normalised O is the final one.
+    const bool direct = p.direct && (t.flags & kFlagQExclusive) != 0;
+    if (!direct) {
       // The rows are reached through a buffer resource that ends with the tile's last row (stores past it are
       // dropped): per-lane offset = the lane's part (row 4 g2 of a group of eight, channel l32), scalar offset =
       // the rest.  A store instruction covers two whole 128-byte lines.
@@ -440,7 +444,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
                                                 (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db, 0);
         }
     }
-    if (p.o_out) {   // running mode: the merged rows as bf16 as well (half a line per store)
+    if (p.o_out && (p.running || direct)) {   // the final rows as bf16 (half a line per store)
       const int row_bytes = p.hq * D * 2;
       const int n_wave_rows = t.rows - wave_r0;
       const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
@@ -458,7 +462,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     }
     if (row_valid && g2 == 0) {
       const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-      p.lse_part[(int64_t)slot * ((int64_t)p.hq * p.tq) + (int64_t)head * p.tq + t.q_row0 + my_row] = lse;
+      float* dst = direct ? p.lse_out : p.lse_part + (int64_t)slot * ((int64_t)p.hq * p.tq);
+      dst[(int64_t)head * p.tq + t.q_row0 + my_row] = lse;
     }
     uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block (barrier: LDS stages are free)
   }
@@ -475,7 +480,8 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
                     int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
                     int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
                     float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part, void* scratch,
-                    size_t scratch_bytes, void* stream, bool running = false, void* o_out = nullptr) {
+                    size_t scratch_bytes, void* stream, bool running = false, void* o_out = nullptr,
+                    float* lse_out = nullptr) {
   fcp::clear_error();
   if (!q || !k || !v || !cu_seqlens_kv || !o_part || !lse_part || !scratch)
     return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: null pointer");
@@ -500,6 +506,13 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   if (cap > INT32_MAX / 64) return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_fwd_step: too many tiles");
   // two heads of one KV head per unit when the heads pair up, else twice the rows for one head
   const int head_pair = ((hq / hkv) % 2 == 0) ? 1 : 0;
+  const bool direct = lse_out != nullptr;
+  if (direct) {   // which rows get their final result from one unit, which are merged from partials
+    const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, n_parts, true, q_limit, nullptr, work, n_work,
+                                           cu_seqlens_kv, n_seqs, tq, tkv, fcp::fwd_q_state(scratch, n_work, tq, tkv, n_parts),
+                                           nullptr, nullptr, nullptr, nullptr, hq * head_dim, hkv * head_dim, st);
+    if (rcs != FCP_OK) return rcs;
+  }
   int rc = fcp::launch_schedule(false, head_pair ? fcp::kFwdBM / 2 : fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, q_limit, nullptr, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
                                 running ? nullptr : lse_part, (int64_t)n_parts * hq * tq, st);
   if (rc != FCP_OK) return rc;
@@ -513,6 +526,8 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   p.q_limit = q_limit;
   p.running = running ? 1 : 0;
   p.o_out = (uint16_t*)o_out;
+  p.lse_out = lse_out;
+  p.direct = direct ? 1 : 0;
   p.tq = tq; p.hq = hq; p.hkv = hkv;
   p.head_pair = head_pair;
   p.scale_log2 = softmax_scale * 1.4426950408889634f;
@@ -566,4 +581,17 @@ extern "C" int fcp_attn_fwd_step_running(const void* q, const void* k, const voi
   }
   return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, 1, tq, tkv, hq, hkv, head_dim, softmax_scale, q_limit,
                   o_run, lse_run, scratch, scratch_bytes, stream, true, o_out);
+}
+
+extern "C" int fcp_attn_fwd_step_direct(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                                        int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                                        int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                                        float softmax_scale, const int32_t* q_limit, float* o_part, float* lse_part,
+                                        void* o, float* lse, void* scratch, size_t scratch_bytes, void* stream) {
+  if (!o || !lse || (reinterpret_cast<uintptr_t>(o) & 15u)) {
+    fcp::clear_error();
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step_direct: o / lse NULL or o not 16-byte aligned");
+  }
+  return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, n_parts, tq, tkv, hq, hkv, head_dim, softmax_scale,
+                  q_limit, o_part, lse_part, scratch, scratch_bytes, stream, false, o, lse);
 }

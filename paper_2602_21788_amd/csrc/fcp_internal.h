@@ -134,10 +134,12 @@ int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int3
                         int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
                         const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream);
 
-// Direct mode of the backward: one state byte per query row and per pool key (0 untouched, 1 accumulated in fp32 -
-// the accumulator row is cleared here -, 2 written directly as bf16 by the unit that owns it).
-int launch_row_states(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from, const fcp_work_desc* work,
-                      int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
+// Direct modes: one state byte per query row and (backward: kv_state not NULL) per pool key: 0 untouched, 1 several
+// work items contribute (backward: accumulated in fp32, the accumulator row is cleared here when the accumulators are
+// given; forward: partial results, merged afterwards), 2 written directly as bf16 by the unit that owns it.
+// n_parts / check_step: the validity rules of the list the states go with.
+int launch_row_states(int64_t kv_row_bytes, int32_t n_parts, bool check_step, const int32_t* q_limit,
+                      const int32_t* k_from, const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                       uint8_t* q_state, uint8_t* kv_state, float* dq_acc, float* dk_acc, float* dv_acc,
                       int32_t q_row_elems, int32_t kv_row_elems, hipStream_t stream);
 
@@ -148,6 +150,11 @@ inline uint8_t* bwd_q_state(void* scratch, int64_t n_work, int32_t tq, int32_t t
 }
 inline uint8_t* bwd_kv_state(void* scratch, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq) {
   return bwd_q_state(scratch, n_work, tq, tkv, hq) + pad_to((size_t)tq, 256);
+}
+
+// The forward's row states follow its tile list in its scratch buffer.
+inline uint8_t* fwd_q_state(void* scratch, int64_t n_work, int32_t tq, int32_t tkv, int32_t n_parts) {
+  return static_cast<uint8_t*>(scratch) + sched_region_bytes(n_work, q_tile_cap(tq, tkv, n_work, n_parts));
 }
 
 }  // namespace fcp

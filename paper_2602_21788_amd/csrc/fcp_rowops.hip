@@ -31,13 +31,14 @@ template <int D>
 __global__ __launch_bounds__(256) void merge_kernel(const float* __restrict__ o_part,
                                                     const float* __restrict__ lse_part, int n_parts,
                                                     int tq, int hq, uint32_t* __restrict__ o,
-                                                    float* __restrict__ lse) {
+                                                    float* __restrict__ lse, const uint8_t* __restrict__ q_state) {
   constexpr int TPR = D / 8;              // threads per (row, head)
   constexpr int ROWS = 256 / TPR;         // rows per block
   const int h = blockIdx.y;
   const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
   const int c8 = threadIdx.x % TPR;
   if (row >= tq) return;
+  if (q_state && q_state[row] == 2) return;   // direct mode: the forward kernel wrote this row's O and LSE itself
   const int64_t lse_stride = (int64_t)hq * tq;
   const int64_t o_stride = (int64_t)tq * hq * D;
   float ls[kMaxParts];
@@ -155,8 +156,8 @@ using fcp::fail;
 
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-extern "C" int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
-                             int32_t hq, int32_t head_dim, void* o, float* lse, void* stream) {
+static int lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
+                     int32_t hq, int32_t head_dim, void* o, float* lse, void* stream, const uint8_t* q_state) {
   fcp::clear_error();
   if (!o_part || !lse_part || !o || !lse) return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge: null pointer");
   if (tq < 0 || hq < 1 || n_parts < 1) return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge: bad sizes");
@@ -168,13 +169,29 @@ extern "C" int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t
   hipStream_t st = (hipStream_t)stream;
   if (head_dim == 128) {
     dim3 grid((tq + 15) / 16, hq);
-    hipLaunchKernelGGL(fcp::merge_kernel<128>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse);
+    hipLaunchKernelGGL(fcp::merge_kernel<128>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse, q_state);
   } else {
     dim3 grid((tq + 31) / 32, hq);
-    hipLaunchKernelGGL(fcp::merge_kernel<64>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse);
+    hipLaunchKernelGGL(fcp::merge_kernel<64>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse, q_state);
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
+}
+
+extern "C" int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
+                             int32_t hq, int32_t head_dim, void* o, float* lse, void* stream) {
+  return lse_merge(o_part, lse_part, n_parts, tq, hq, head_dim, o, lse, stream, nullptr);
+}
+
+extern "C" int fcp_lse_merge_direct(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
+                                    int32_t tkv, int32_t hq, int32_t head_dim, void* o, float* lse, void* scratch,
+                                    int64_t n_work, void* stream) {
+  if (!scratch || tkv < 1 || n_work < 0) {
+    fcp::clear_error();
+    return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge_direct: scratch is NULL or bad sizes");
+  }
+  return lse_merge(o_part, lse_part, n_parts, tq, hq, head_dim, o, lse, stream,
+                   fcp::fwd_q_state(scratch, n_work, tq, tkv, n_parts));
 }
 
 extern "C" int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, int32_t head_dim,

@@ -345,7 +345,8 @@ __global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
 // afterwards - its accumulator row is cleared here; 2: one unit owns it and writes the final bf16 row itself.  The
 // states follow the same exclusivity flags the kernels act on.  One wave per row.
 __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
-    int32_t max_seg_keys, const MaskTables m, const fcp_work_desc* __restrict__ work, int32_t n_work,
+    int32_t max_seg_keys, int32_t n_parts, int check_step, int32_t n_kv_rows, const MaskTables m,
+    const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, uint8_t* __restrict__ q_state,
     uint8_t* __restrict__ kv_state, float* __restrict__ dq_acc, float* __restrict__ dk_acc, float* __restrict__ dv_acc,
     int32_t q_row_elems, int32_t kv_row_elems) {
@@ -355,7 +356,7 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   for (int32_t i = tid; i < n_work; i += kSchedThreads) {
     const fcp_work_desc a = work[i];
-    const bool ok = item_valid(a, cu, n_seqs, tq, tkv, 1, false, max_seg_keys);
+    const bool ok = item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys);
     stage_item(s_rng[i], a, ok);
     s_vis[i][0] = ok ? visible_len(m, a, 0, a.q_len - 1) : 0;
     s_vis[i][1] = ok && a.n_seg > 1 ? visible_len(m, a, 1, a.q_len - 1) : 0;
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
   for (int32_t i = tid; i < n_work; i += kSchedThreads) s_fl[i] = (uint8_t)exclusive_flags(s_rng, i, n_work);
   __syncthreads();
 
-  const int64_t n_rows = (int64_t)tq + tkv;
+  const int64_t n_rows = (int64_t)tq + n_kv_rows;     // (the forward classifies its query rows only)
   const int64_t wave0 = (int64_t)blockIdx.x * (kSchedThreads / 64) + (tid >> 6);
   const int64_t wstride = (int64_t)gridDim.x * (kSchedThreads / 64);
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -397,7 +398,7 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
     const int state = total == 0 ? 0 : (total == 1 && any_own != 0) ? 2 : 1;
     if (r < tq) {
       if (lane == 0) q_state[r] = (uint8_t)state;
-      if (state == 1) {
+      if (state == 1 && dq_acc) {
         float4* row = reinterpret_cast<float4*>(dq_acc + r * q_row_elems);
         for (int32_t e = lane; e < q_row_elems / 4; e += 64) row[e] = zero;
       }
@@ -415,17 +416,20 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
 
 }  // namespace
 
-int launch_row_states(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from, const fcp_work_desc* work,
+int launch_row_states(int64_t kv_row_bytes, int32_t n_parts, bool check_step, const int32_t* q_limit,
+                      const int32_t* k_from, const fcp_work_desc* work,
                       int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                       uint8_t* q_state, uint8_t* kv_state, float* dq_acc, float* dk_acc, float* dv_acc,
                       int32_t q_row_elems, int32_t kv_row_elems, hipStream_t stream) {
   if (n_work > kMaxExclusiveScan)
-    return fail(FCP_ERR_UNSUPPORTED, "direct backward: more than %d work items (use the accumulating entry point)", kMaxExclusiveScan);
-  int64_t blocks = ((int64_t)tq + tkv + kSchedThreads / 64 - 1) / (kSchedThreads / 64);
-  if (blocks > 2048) blocks = 2048;
+    return fail(FCP_ERR_UNSUPPORTED, "direct mode: more than %d work items (use the plain entry point)", kMaxExclusiveScan);
+  const int32_t n_kv_rows = kv_state ? tkv : 0;
+  int64_t blocks = ((int64_t)tq + n_kv_rows + kSchedThreads / 64 - 1) / (kSchedThreads / 64);
+  if (blocks > 512) blocks = 512;      // every block stages the whole work list first: few blocks, several rows per wave
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(row_state_kernel, dim3((unsigned)blocks), dim3(kSchedThreads), 0, stream,
-                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work,
+                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), n_parts, check_step ? 1 : 0, n_kv_rows,
+                     MaskTables{q_limit, k_from}, work,
                      (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, q_state, kv_state, dq_acc, dk_acc, dv_acc,
                      q_row_elems, kv_row_elems);
   FCP_HIP_CHECK(hipGetLastError());
@@ -503,7 +507,8 @@ extern "C" size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t 
            fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, 1 << 20)) +
            fcp::pad_to((size_t)hq * (size_t)tq * 8, 256) +
            fcp::pad_to((size_t)tq, 256) + fcp::pad_to((size_t)tkv, 256);   // + row states of the direct mode
-  return fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, n_parts));
+  return fcp::sched_region_bytes(n_work, fcp::q_tile_cap(tq, tkv, n_work, n_parts)) +
+         fcp::pad_to((size_t)tq, 256);                                  // + row states of the direct mode
 }
 
 extern "C" int fcp_scratch_status(const void* scratch, void* stream, int32_t* n_tiles, int32_t* n_rejected) {

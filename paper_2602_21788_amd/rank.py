@@ -130,6 +130,19 @@ class RankAttention:
         self.forward_steps(stream)
         self.merge(stream)
 
+    # The same results with the rows that one work item feeds written once, as bf16, by the forward kernel.
+    def forward_steps_direct(self, stream=None):
+        B.fcp_attn_fwd_step_direct(self.q, self.k, self.v, self.cu_d, self.work_d, self.n_parts, self.scale, self.o_part,
+                                   self.lse_part, self.o, self.lse, self.scratch_f,
+                                   q_limit=self.q_limit_d if self.spans is not None else None, stream=stream)
+
+    def merge_direct(self, stream=None):
+        B.fcp_lse_merge_direct(self.o_part, self.lse_part, self.o, self.lse, self.tkv, self.scratch_f, self.n_work, stream)
+
+    def forward_direct(self, stream=None):
+        self.forward_steps_direct(stream)
+        self.merge_direct(stream)
+
     def zero_grads(self):
         self.dq_acc.zero_(); self.dk_acc.zero_(); self.dv_acc.zero_()
 
@@ -185,11 +198,16 @@ class RankAttention:
             tot += n * a + n * (n + 1) // 2
         return tot
 
-    def merge_bytes(self) -> int:
+    def merge_bytes(self, direct: bool = False) -> int:
         """Algorithmic bytes of fcp_lse_merge: per row and head, each contributing slot is read
-        once (D fp32 + its LSE), every slot's LSE is read, and O (bf16) + LSE are written."""
+        once (D fp32 + its LSE), every slot's LSE is read, and O (bf16) + LSE are written.  direct: those of
+        fcp_lse_merge_direct, which skips the rows that exactly one work item feeds (one state byte per row is read)."""
         parts_per_row = np.zeros(self.tq, np.int64)
         for w in self.work:
             parts_per_row[int(w["q_local_off"]):int(w["q_local_off"]) + int(w["q_len"])] += 1
         D = self.D
+        if direct:
+            merged = parts_per_row != 1
+            return int(self.hq * (parts_per_row[merged].sum() * (D * 4) + merged.sum() * (self.n_parts * 4 + D * 2 + 4))
+                       + self.tq * self.hq)
         return int(self.hq * (parts_per_row.sum() * (D * 4) + self.tq * (self.n_parts * 4 + D * 2 + 4)))

@@ -51,6 +51,22 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
     assert np.isfinite(O).all() and np.isfinite(LSE).all(), label
     assert res["O"] <= TOL_BF16_REL, (label, res)
     assert res["LSE"] <= TOL_LSE_ABS, (label, res)
+    # The direct forward (rows fed by one work item written once by the kernel, the others merged) on poisoned
+    # buffers: the same bar, and the same values as partial results + merge up to the bf16 rounding of O.
+    for t in (ra.o, ra.lse, ra.o_part, ra.lse_part):
+        t.fill_(float("nan"))
+    ra.forward_direct()
+    torch.cuda.synchronize()
+    assert __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_f)[1] == 0, label
+    O_d = bf16_tensor_to_f64(ra.o)
+    LSE_d = ra.lse.cpu().numpy().astype(np.float64).T
+    assert np.isfinite(O_d).all() and not np.isnan(LSE_d).any(), (label, "direct forward")
+    res["O_direct"] = rel_err(O_d, O_ref)
+    res["LSE_direct"] = float(np.abs(LSE_d - LSE_ref).max())
+    assert res["O_direct"] <= TOL_BF16_REL and res["LSE_direct"] <= TOL_LSE_ABS, (label, "direct forward", res)
+    assert rel_err(O_d, O) <= 2.0 ** -7 and np.abs(LSE_d - LSE).max() <= 1e-5, (label, "direct vs partial + merge")
+    ra.forward()                      # (the partial results are looked at below)
+    torch.cuda.synchronize()
     if check_partials:
         qf, kf, vf = (synth.bf16_bits_to_f64(x) for x in (q, k, v))
         Op_ref, Lp_ref = oplan.rank_partials(qf, kf, vf, wl.cu_seqlens, ochunks, owork, rank, wl.softmax_scale, span_id=sid)

@@ -104,6 +104,14 @@ def test_cfg2_full_size_sampled():
     dQ, dK, dV = (bf16_tensor_to_f64(x) for x in (ra.dq, ra.dk, ra.dv))
     for x in (O, LSE, dQ, dK, dV):
         assert np.isfinite(x).all()
+    # The direct forward (what bench.py times) on poisoned buffers: every element against partial results + merge.
+    for t in (ra.o, ra.lse, ra.o_part, ra.lse_part):
+        t.fill_(float("nan"))
+    ra.forward_direct()
+    torch.cuda.synchronize()
+    O_d, LSE_d = bf16_tensor_to_f64(ra.o), ra.lse.cpu().numpy().astype(np.float64).T
+    assert np.isfinite(O_d).all() and np.isfinite(LSE_d).all()
+    assert rel_err(O_d, O) <= 2.0 ** -7 and np.abs(LSE_d - LSE).max() <= 1e-5
     # The direct backward (what bench.py times) on poisoned buffers: every element against the accumulating path,
     # which is checked against the oracle below - the arithmetic is the same up to the order of the fp32 atomics.
     for t in (ra.dq_acc, ra.dk_acc, ra.dv_acc, ra.dq, ra.dk, ra.dv):
