@@ -47,6 +47,9 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             from . import build as _build
             _build.build()
+        # torch first: it ships its own HIP runtime, and a process must not end up with two (libfcp.so loaded before
+        # torch would bind to the system's copy, and the second runtime to start finds no device)
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         P, I32, I64, F, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
         L.fcp_last_error.restype = ctypes.c_char_p
