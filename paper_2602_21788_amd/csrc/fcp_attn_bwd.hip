@@ -463,20 +463,29 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   void* region_kv = scratch;
   void* region_q = static_cast<char*>(scratch) + fcp::sched_region_bytes(n_work, cap_kv);
   float* stats = reinterpret_cast<float*>(static_cast<char*>(region_q) + fcp::sched_region_bytes(n_work, cap_q));
-  if (direct) {   // where every row's result comes from; clears the accumulator rows that are accumulated into
-    const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, 1, false, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs,
-                                           tq, tkv, fcp::bwd_q_state(scratch, n_work, tq, tkv, hq),
-                                           fcp::bwd_kv_state(scratch, n_work, tq, tkv, hq), dq_acc, dk_acc, dv_acc,
-                                           hq * head_dim, hkv * head_dim, st);
-    if (rcs != FCP_OK) return rcs;
+  // direct mode: where every row's result comes from (and the accumulator rows that are accumulated into cleared),
+  // on extra blocks of the scheduling launch
+  fcp::RowStates rs{};
+  if (direct) {
+    rs.q_state = fcp::bwd_q_state(scratch, n_work, tq, tkv, hq);
+    rs.kv_state = fcp::bwd_kv_state(scratch, n_work, tq, tkv, hq);
+    rs.dq_acc = dq_acc; rs.dk_acc = dk_acc; rs.dv_acc = dv_acc;
+    rs.q_row_elems = hq * head_dim; rs.kv_row_elems = hkv * head_dim;
+    rs.n_parts = 1; rs.check_step = false;
   }
   if (tq == 0 || n_work == 0) {     // nothing to add; the lists are still built so that the status call works
+    if (direct) {
+      const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, rs, q_limit, k_from, work, n_work, cu_seqlens_kv,
+                                             n_seqs, tq, tkv, st);
+      if (rcs != FCP_OK) return rcs;
+    }
     int rc0 = fcp::launch_schedule(true, fcp::kBwdBN, fcp::kBwdBM, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_kv, region_kv, nullptr, 0, st);
     if (rc0 != FCP_OK) return rc0;
     return fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   }
   int rc = fcp::launch_schedule_bwd((int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv,
-                                    cap_kv, region_kv, cap_q, region_q, lse, delta, (int64_t)hq * tq, stats, st);
+                                    cap_kv, region_kv, cap_q, region_q, lse, delta, (int64_t)hq * tq, stats, st,
+                                    direct ? &rs : nullptr);
   if (rc != FCP_OK) return rc;
 
   fcp::BwdParams p;

@@ -507,14 +507,16 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   // two heads of one KV head per unit when the heads pair up, else twice the rows for one head
   const int head_pair = ((hq / hkv) % 2 == 0) ? 1 : 0;
   const bool direct = lse_out != nullptr;
-  if (direct) {   // which rows get their final result from one unit, which are merged from partials
-    const int rcs = fcp::launch_row_states((int64_t)hkv * head_dim * 2, n_parts, true, q_limit, nullptr, work, n_work,
-                                           cu_seqlens_kv, n_seqs, tq, tkv, fcp::fwd_q_state(scratch, n_work, tq, tkv, n_parts),
-                                           nullptr, nullptr, nullptr, nullptr, hq * head_dim, hkv * head_dim, st);
-    if (rcs != FCP_OK) return rcs;
+  // direct mode: which rows get their final result from one unit and which are merged from partials is worked out on
+  // extra blocks of the scheduling launch
+  fcp::RowStates rs{};
+  if (direct) {
+    rs.q_state = fcp::fwd_q_state(scratch, n_work, tq, tkv, n_parts);
+    rs.q_row_elems = hq * head_dim; rs.kv_row_elems = hkv * head_dim;
+    rs.n_parts = n_parts; rs.check_step = true;
   }
   int rc = fcp::launch_schedule(false, head_pair ? fcp::kFwdBM / 2 : fcp::kFwdBM, fcp::kFwdBN, (int64_t)hkv * head_dim * 2, q_limit, nullptr, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts, cap, scratch,
-                                running ? nullptr : lse_part, (int64_t)n_parts * hq * tq, st);
+                                running ? nullptr : lse_part, (int64_t)n_parts * hq * tq, st, direct ? &rs : nullptr);
   if (rc != FCP_OK) return rc;
   if (tq == 0 || n_work == 0) return FCP_OK;
 

@@ -113,6 +113,8 @@ inline const Tile* sched_tiles(const void* region, int64_t n_work) {
 
 static_assert(kBwdBN == 4 * 32, "KTile keeps four key groups");
 
+struct RowStates;   // direct modes, see below
+
 // Builds one tile list in `region` (tiles of `tile` keys if `key_tiles`, else of `tile` query rows;
 // `inner` is the block size of the other dimension used for the cost; kv_row_bytes = hkv*D*2 bounds
 // the segment length so that byte offsets inside a segment fit 31 bits) and, when
@@ -124,7 +126,7 @@ int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, int64_t kv_row_
                     const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
-                    int64_t lse_fill_n, hipStream_t stream);
+                    int64_t lse_fill_n, hipStream_t stream, const RowStates* states = nullptr);
 
 // Everything that precedes the backward's attention kernels in one launch: both tile lists (key tiles of kBwdBN
 // keys in region_kv, query tiles of kDqBM rows in region_q) and the row statistics (stats: two planes of n_stats
@@ -132,16 +134,27 @@ int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, int64_t kv_row_
 int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from,
                         const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
                         int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
-                        const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream);
+                        const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream,
+                        const RowStates* states = nullptr);
 
 // Direct modes: one state byte per query row and (backward: kv_state not NULL) per pool key: 0 untouched, 1 several
-// work items contribute (backward: accumulated in fp32, the accumulator row is cleared here when the accumulators are
+// work items contribute (backward: accumulated in fp32, the accumulator row is cleared when the accumulators are
 // given; forward: partial results, merged afterwards), 2 written directly as bf16 by the unit that owns it.
-// n_parts / check_step: the validity rules of the list the states go with.
-int launch_row_states(int64_t kv_row_bytes, int32_t n_parts, bool check_step, const int32_t* q_limit,
-                      const int32_t* k_from, const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
-                      uint8_t* q_state, uint8_t* kv_state, float* dq_acc, float* dk_acc, float* dv_acc,
-                      int32_t q_row_elems, int32_t kv_row_elems, hipStream_t stream);
+// n_parts / check_step: the validity rules of the list the states go with.  The scheduling launches below compute
+// them on additional blocks when `states` is given; launch_row_states() is the same work as a launch of its own.
+struct RowStates {
+  uint8_t* q_state;
+  uint8_t* kv_state;
+  float* dq_acc;
+  float* dk_acc;
+  float* dv_acc;
+  int32_t q_row_elems, kv_row_elems;
+  int32_t n_parts;
+  bool check_step;
+};
+int launch_row_states(int64_t kv_row_bytes, const RowStates& rs, const int32_t* q_limit, const int32_t* k_from,
+                      const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                      int32_t tq, int32_t tkv, hipStream_t stream);
 
 // Where the row states live in the backward's scratch buffer (after the two lists and the statistics planes).
 inline uint8_t* bwd_q_state(void* scratch, int64_t n_work, int32_t tq, int32_t tkv, int32_t hq) {

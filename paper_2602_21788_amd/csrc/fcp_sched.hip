@@ -163,11 +163,11 @@ __device__ void build_list(
     int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
     const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
-    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles) {
+    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
+    int32_t (*s_rng)[7]) {               // LDS, kMaxExclusiveScan rows: seq (-1 = invalid), q range, two key ranges
   __shared__ int32_t s_wave[kSchedThreads / 64];
   __shared__ int32_t s_hist[kBuckets];
   __shared__ int32_t s_max, s_rej, s_carry;
-  __shared__ int32_t s_rng[kMaxExclusiveScan][7];   // seq (-1 = invalid), q range, two key ranges
   const int tid = threadIdx.x;
   if (tid == 0) { s_max = 0; s_rej = 0; s_carry = 0; }
   for (int b = tid; b < kBuckets; b += kSchedThreads) s_hist[b] = 0;
@@ -293,70 +293,35 @@ __device__ void build_list(
   }
 }
 
-// Forward: block 0 builds the query-tile list, the other blocks pre-fill the partial LSE with -inf.
-__global__ __launch_bounds__(kSchedThreads) void sched_kernel(
-    int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
-    const fcp_work_desc* __restrict__ work, int32_t n_work,
-    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
-    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
-    float* lse_fill, int64_t lse_fill_n) {
-  if (blockIdx.x > 0) {
-    const int64_t stride = (int64_t)(gridDim.x - 1) * kSchedThreads;
-    for (int64_t i = (int64_t)(blockIdx.x - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
-      lse_fill[i] = -INFINITY;
-    return;
-  }
-  build_list(backward, check_step, tile, inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, n_parts, tile_cap,
-             hdr, item_off, item_flags, tiles);
-}
-
-// Backward: one launch for everything that precedes the two attention kernels.  Block 0 builds the key-tile list
-// (dK/dV kernel), block 1 the query-tile list (dQ kernel), the other blocks write the row statistics in the form
-// the kernels consume: plane 0 = -LSE log2 e (-inf for a row without keys, so that its probabilities vanish),
-// plane 1 = -delta.
-struct ListJob {
-  int32_t tile, inner, tile_cap;
-  SchedHeader* hdr;
-  int32_t* item_off;
-  int32_t* item_flags;
-  Tile* tiles;
-};
-__global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
-    const ListJob kv, const ListJob qt, int32_t max_seg_keys, const MaskTables m,
-    const fcp_work_desc* __restrict__ work, int32_t n_work,
-    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv,
-    const float* __restrict__ lse, const float* __restrict__ delta, int64_t n_stats, float* __restrict__ stats) {
-  if (blockIdx.x >= 2) {
-    const int64_t stride = (int64_t)(gridDim.x - 2) * kSchedThreads;
-    for (int64_t i = (int64_t)(blockIdx.x - 2) * kSchedThreads + threadIdx.x; i < n_stats; i += stride) {
-      const float l = lse[i];
-      stats[i] = l == -INFINITY ? -INFINITY : -l * 1.4426950408889634f;
-      stats[n_stats + i] = -delta[i];
-    }
-    return;
-  }
-  const ListJob& j = blockIdx.x == 0 ? kv : qt;
-  build_list(blockIdx.x == 0 ? 1 : 0, 0, j.tile, j.inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, 1,
-             j.tile_cap, j.hdr, j.item_off, j.item_flags, j.tiles);
-}
-
 // Direct mode of the backward: where does the result of every query row / pool key come from?  State 0: no unit of
 // this launch touches it (the result is zero); 1: it is accumulated in fp32 (several units, atomics) and converted
 // afterwards - its accumulator row is cleared here; 2: one unit owns it and writes the final bf16 row itself.  The
 // states follow the same exclusivity flags the kernels act on.  One wave per row.
-__global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
-    int32_t max_seg_keys, int32_t n_parts, int check_step, int32_t n_kv_rows, const MaskTables m,
-    const fcp_work_desc* __restrict__ work, int32_t n_work,
-    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, uint8_t* __restrict__ q_state,
-    uint8_t* __restrict__ kv_state, float* __restrict__ dq_acc, float* __restrict__ dk_acc, float* __restrict__ dv_acc,
-    int32_t q_row_elems, int32_t kv_row_elems) {
-  __shared__ int32_t s_rng[kMaxExclusiveScan][7];
-  __shared__ int32_t s_vis[kMaxExclusiveScan][2];   // keys of each segment that the item's last row sees
-  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+struct RowStateJob {
+  uint8_t* q_state;        // NULL: no row states in this launch
+  uint8_t* kv_state;       // NULL: query rows only (forward)
+  float* dq_acc;           // accumulators whose state-1 rows are cleared, or NULL
+  float* dk_acc;
+  float* dv_acc;
+  int32_t q_row_elems, kv_row_elems;
+  int32_t n_parts, check_step;   // the validity rules of the list the states go with
+};
+// The blocks `first` .. `first + count - 1` of the launch share the rows; LDS arrays come from the kernel.
+__device__ void row_states(
+    int first, int count, const RowStateJob& job, int32_t max_seg_keys, const MaskTables& m,
+    const fcp_work_desc* __restrict__ work, int32_t n_work, const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq,
+    int32_t tkv, int32_t (*s_rng)[7], int32_t (*s_vis)[2], uint8_t* s_fl) {
+  uint8_t* __restrict__ q_state = job.q_state;
+  uint8_t* __restrict__ kv_state = job.kv_state;
+  float* __restrict__ dq_acc = job.dq_acc;
+  float* __restrict__ dk_acc = job.dk_acc;
+  float* __restrict__ dv_acc = job.dv_acc;
+  const int32_t q_row_elems = job.q_row_elems, kv_row_elems = job.kv_row_elems;
+  const int32_t n_kv_rows = kv_state ? tkv : 0;
   const int tid = threadIdx.x, lane = tid & 63;
   for (int32_t i = tid; i < n_work; i += kSchedThreads) {
     const fcp_work_desc a = work[i];
-    const bool ok = item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys);
+    const bool ok = item_valid(a, cu, n_seqs, tq, tkv, job.n_parts, job.check_step != 0, max_seg_keys);
     stage_item(s_rng[i], a, ok);
     s_vis[i][0] = ok ? visible_len(m, a, 0, a.q_len - 1) : 0;
     s_vis[i][1] = ok && a.n_seg > 1 ? visible_len(m, a, 1, a.q_len - 1) : 0;
@@ -366,8 +331,8 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
   __syncthreads();
 
   const int64_t n_rows = (int64_t)tq + n_kv_rows;     // (the forward classifies its query rows only)
-  const int64_t wave0 = (int64_t)blockIdx.x * (kSchedThreads / 64) + (tid >> 6);
-  const int64_t wstride = (int64_t)gridDim.x * (kSchedThreads / 64);
+  const int64_t wave0 = (int64_t)(blockIdx.x - first) * (kSchedThreads / 64) + (tid >> 6);
+  const int64_t wstride = (int64_t)count * (kSchedThreads / 64);
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int64_t r = wave0; r < n_rows; r += wstride) {
     int32_t cnt = 0, own = 0;            // covering (item, segment) pairs among this lane's items; flags bit of the last
@@ -414,24 +379,112 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
   }
 }
 
+// The row states alone (launches that build no list).
+__global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
+    const RowStateJob job, int32_t max_seg_keys, const MaskTables m, const fcp_work_desc* __restrict__ work,
+    int32_t n_work, const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv) {
+  __shared__ int32_t s_rng[kMaxExclusiveScan][7];
+  __shared__ int32_t s_vis[kMaxExclusiveScan][2];   // keys of each segment that the item's last row sees
+  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+  row_states(0, gridDim.x, job, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, s_rng, s_vis, s_fl);
+}
+
+// Forward: block 0 builds the query-tile list, the next `fill_blocks` blocks pre-fill the partial LSE with -inf,
+// the blocks after those classify the rows (direct mode).
+__global__ __launch_bounds__(kSchedThreads) void sched_kernel(
+    int backward, int check_step, int32_t tile, int32_t inner, int32_t max_seg_keys, const MaskTables m,
+    const fcp_work_desc* __restrict__ work, int32_t n_work,
+    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
+    int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
+    float* lse_fill, int64_t lse_fill_n, int fill_blocks, const RowStateJob states) {
+  __shared__ int32_t s_rng[kMaxExclusiveScan][7];
+  __shared__ int32_t s_vis[kMaxExclusiveScan][2];
+  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+  const int b = blockIdx.x;
+  if (b == 0) {
+    build_list(backward, check_step, tile, inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, n_parts, tile_cap,
+               hdr, item_off, item_flags, tiles, s_rng);
+  } else if (b <= fill_blocks) {
+    const int64_t stride = (int64_t)fill_blocks * kSchedThreads;
+    for (int64_t i = (int64_t)(b - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
+      lse_fill[i] = -INFINITY;
+  } else {
+    row_states(1 + fill_blocks, gridDim.x - 1 - fill_blocks, states, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv,
+               s_rng, s_vis, s_fl);
+  }
+}
+
+// Backward: one launch for everything that precedes the two attention kernels.  Block 0 builds the key-tile list
+// (dK/dV kernel), block 1 the query-tile list (dQ kernel), the other blocks write the row statistics in the form
+// the kernels consume: plane 0 = -LSE log2 e (-inf for a row without keys, so that its probabilities vanish),
+// plane 1 = -delta.
+struct ListJob {
+  int32_t tile, inner, tile_cap;
+  SchedHeader* hdr;
+  int32_t* item_off;
+  int32_t* item_flags;
+  Tile* tiles;
+};
+__global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
+    const ListJob kv, const ListJob qt, int32_t max_seg_keys, const MaskTables m,
+    const fcp_work_desc* __restrict__ work, int32_t n_work,
+    const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv,
+    const float* __restrict__ lse, const float* __restrict__ delta, int64_t n_stats, float* __restrict__ stats,
+    int stat_blocks, const RowStateJob states) {
+  __shared__ int32_t s_rng[kMaxExclusiveScan][7];
+  __shared__ int32_t s_vis[kMaxExclusiveScan][2];
+  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+  const int b = blockIdx.x;
+  if (b < 2) {
+    const ListJob& j = b == 0 ? kv : qt;
+    build_list(b == 0 ? 1 : 0, 0, j.tile, j.inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, 1,
+               j.tile_cap, j.hdr, j.item_off, j.item_flags, j.tiles, s_rng);
+  } else if (b < 2 + stat_blocks) {
+    const int64_t stride = (int64_t)stat_blocks * kSchedThreads;
+    for (int64_t i = (int64_t)(b - 2) * kSchedThreads + threadIdx.x; i < n_stats; i += stride) {
+      const float l = lse[i];
+      stats[i] = l == -INFINITY ? -INFINITY : -l * 1.4426950408889634f;
+      stats[n_stats + i] = -delta[i];
+    }
+  } else {   // direct mode: the row states, and the accumulator rows that are accumulated into cleared
+    row_states(2 + stat_blocks, gridDim.x - 2 - stat_blocks, states, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv,
+               s_rng, s_vis, s_fl);
+  }
+}
+
 }  // namespace
 
-int launch_row_states(int64_t kv_row_bytes, int32_t n_parts, bool check_step, const int32_t* q_limit,
-                      const int32_t* k_from, const fcp_work_desc* work,
-                      int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
-                      uint8_t* q_state, uint8_t* kv_state, float* dq_acc, float* dk_acc, float* dv_acc,
-                      int32_t q_row_elems, int32_t kv_row_elems, hipStream_t stream) {
-  if (n_work > kMaxExclusiveScan)
-    return fail(FCP_ERR_UNSUPPORTED, "direct mode: more than %d work items (use the plain entry point)", kMaxExclusiveScan);
-  const int32_t n_kv_rows = kv_state ? tkv : 0;
+static int row_state_blocks(int32_t tq, int32_t n_kv_rows) {
   int64_t blocks = ((int64_t)tq + n_kv_rows + kSchedThreads / 64 - 1) / (kSchedThreads / 64);
   if (blocks > 512) blocks = 512;      // every block stages the whole work list first: few blocks, several rows per wave
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(row_state_kernel, dim3((unsigned)blocks), dim3(kSchedThreads), 0, stream,
-                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), n_parts, check_step ? 1 : 0, n_kv_rows,
-                     MaskTables{q_limit, k_from}, work,
-                     (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, q_state, kv_state, dq_acc, dk_acc, dv_acc,
-                     q_row_elems, kv_row_elems);
+  return blocks < 1 ? 1 : (int)blocks;
+}
+
+static RowStateJob make_job(const RowStates* rs) {
+  RowStateJob j{};
+  if (rs) {
+    j.q_state = rs->q_state; j.kv_state = rs->kv_state;
+    j.dq_acc = rs->dq_acc; j.dk_acc = rs->dk_acc; j.dv_acc = rs->dv_acc;
+    j.q_row_elems = rs->q_row_elems; j.kv_row_elems = rs->kv_row_elems;
+    j.n_parts = rs->n_parts; j.check_step = rs->check_step ? 1 : 0;
+  }
+  return j;
+}
+
+int check_row_states(int64_t n_work) {
+  if (n_work > kMaxExclusiveScan)
+    return fail(FCP_ERR_UNSUPPORTED, "direct mode: more than %d work items (use the plain entry point)", kMaxExclusiveScan);
+  return FCP_OK;
+}
+
+int launch_row_states(int64_t kv_row_bytes, const RowStates& rs, const int32_t* q_limit, const int32_t* k_from,
+                      const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
+                      int32_t tq, int32_t tkv, hipStream_t stream) {
+  int rc = check_row_states(n_work);
+  if (rc != FCP_OK) return rc;
+  hipLaunchKernelGGL(row_state_kernel, dim3((unsigned)row_state_blocks(tq, rs.kv_state ? tkv : 0)), dim3(kSchedThreads), 0,
+                     stream, make_job(&rs), (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes),
+                     MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
 }
@@ -451,7 +504,8 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
                     const fcp_work_desc* work, int64_t n_work,
                     const int32_t* cu_seqlens_kv, int32_t n_seqs, int32_t tq, int32_t tkv,
                     int32_t n_parts, int64_t tile_cap, void* region, float* lse_fill,
-                    int64_t lse_fill_n, hipStream_t stream) {
+                    int64_t lse_fill_n, hipStream_t stream, const RowStates* states) {
+  if (states) { const int rcs = check_row_states(n_work); if (rcs != FCP_OK) return rcs; }
   char* base = static_cast<char*>(region);
   SchedHeader* hdr = reinterpret_cast<SchedHeader*>(base);
   int32_t* item_off = reinterpret_cast<int32_t*>(base + sizeof(SchedHeader));
@@ -463,10 +517,11 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
     if (fill_blocks > 1024) fill_blocks = 1024;
     if (fill_blocks < 1) fill_blocks = 1;
   }
-  hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks), dim3(kSchedThreads), 0, stream,
+  const int state_blocks = states ? row_state_blocks(tq, states->kv_state ? tkv : 0) : 0;
+  hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks + state_blocks), dim3(kSchedThreads), 0, stream,
                      backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner,
                      (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
-                     (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n);
+                     (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n, fill_blocks, make_job(states));
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
 }
@@ -474,7 +529,9 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
 int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from,
                         const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
                         int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
-                        const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream) {
+                        const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream,
+                        const RowStates* states) {
+  if (states) { const int rcs = check_row_states(n_work); if (rcs != FCP_OK) return rcs; }
   auto job = [&](void* region, int32_t tile, int32_t inner, int64_t cap) {
     ListJob j;
     j.tile = tile; j.inner = inner; j.tile_cap = (int32_t)cap;
@@ -487,10 +544,12 @@ int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int3
   int64_t stat_blocks = (n_stats + kSchedThreads * 4 - 1) / (kSchedThreads * 4);
   if (stat_blocks > 1024) stat_blocks = 1024;
   if (stat_blocks < 1) stat_blocks = 1;
-  hipLaunchKernelGGL(sched_bwd_kernel, dim3((unsigned)(2 + stat_blocks)), dim3(kSchedThreads), 0, stream,
+  const int state_blocks = states ? row_state_blocks(tq, states->kv_state ? tkv : 0) : 0;
+  hipLaunchKernelGGL(sched_bwd_kernel, dim3((unsigned)(2 + stat_blocks + state_blocks)), dim3(kSchedThreads), 0, stream,
                      job(region_kv, kBwdBN, kBwdBM, cap_kv), job(region_q, kDqBM, kDqBN, cap_q),
                      (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work,
-                     (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, lse, delta, n_stats, stats);
+                     (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, lse, delta, n_stats, stats, (int)stat_blocks,
+                     make_job(states));
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
 }
