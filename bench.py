@@ -31,7 +31,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per fcp_attn_bwd_step(_direct) launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload only.
 MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "accumulate"): 5.66e9,
-                              ("packed32k_lognormal24_h32x8_D128", "direct"): 4.66e9}
+                              ("packed32k_lognormal24_h32x8_D128", "direct"): 4.65e9}
 
 
 def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30, spans=None):
