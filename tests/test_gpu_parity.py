@@ -265,3 +265,52 @@ def test_whole_path_in_a_hip_graph_replays_identically():
         for a, b in zip(got[2:], want[2:]):
             assert torch.isfinite(a.float()).all()
             assert (a.float() - b.float()).abs().max().item() <= 1e-2 * b.float().abs().max().item()
+
+
+def test_direct_entry_points_equal_the_plain_ones_on_random_batches():
+    """Seeded random packed batches (lengths 1 .. 1500, degrees 1 .. 5 with every rank in turn, several head layouts,
+    every third batch with full-attention spans): the direct forward / backward on NaN-filled buffers against the
+    plain entry points on the same device inputs, element by element.  The plain path is what the other tests hold
+    against the oracle; this one is about the row classification (untouched / several items / one owner) agreeing
+    with what the kernels do, for layouts no hand-written case has."""
+    import torch
+    from paper_2602_21788_amd.rank import RankAttention
+    rng = np.random.default_rng(2024)
+    layouts = [(8, 2, 128), (4, 4, 64), (6, 2, 64), (8, 1, 128), (2, 2, 128)]
+    n_cases = 0
+    for case in range(18):
+        n_seq = int(rng.integers(1, 7))
+        lens = [int(x) for x in rng.integers(1, 1500, n_seq)]
+        deg = [int(min(rng.integers(1, 6), max(1, L // 2))) for L in lens]
+        hq, hkv, D = layouts[case % len(layouts)]
+        spans = None
+        if case % 3 == 2:
+            spans = []
+            for s, L in enumerate(lens):
+                if L >= 40:
+                    a = int(rng.integers(0, L - 30))
+                    spans.append((s, a, int(rng.integers(2, min(300, L - a)))))
+            spans = spans or None
+        rank = case % max(deg)
+        ra = RankAttention(lens, deg, rank, hq, hkv, D, spans=spans)
+        if ra.tq == 0:
+            continue
+        _say(f"random batch {case}: lens {lens} degrees {deg} rank {rank} heads {hq}/{hkv} D {D} spans {spans}")
+        ra.set_random_inputs(case)
+        ra.forward(); ra.backward()
+        torch.cuda.synchronize()
+        plain = [t.clone() for t in (ra.o, ra.lse, ra.dq, ra.dk, ra.dv)]
+        for t in (ra.o, ra.lse, ra.o_part, ra.lse_part, ra.dq_acc, ra.dk_acc, ra.dv_acc, ra.dq, ra.dk, ra.dv):
+            t.fill_(float("nan"))
+        ra.forward_direct(); ra.backward_direct()
+        torch.cuda.synchronize()
+        for name, a, b in zip(("O", "LSE", "dQ", "dK", "dV"), plain, (ra.o, ra.lse, ra.dq, ra.dk, ra.dv)):
+            a, b = a.double(), b.double()
+            assert not torch.isnan(b).any(), (case, name)
+            assert torch.equal(torch.isinf(a), torch.isinf(b)), (case, name)      # LSE = -inf for rows without keys
+            fin = torch.isfinite(a)
+            scale = float(a[fin].abs().max()) if fin.any() else 1.0
+            err = float((a[fin] - b[fin]).abs().max()) / max(scale, 1e-30) if fin.any() else 0.0
+            assert err <= (1e-5 if name == "LSE" else 2.0 ** -7), (case, name, err)
+        n_cases += 1
+    assert n_cases >= 12
