@@ -7,6 +7,10 @@
  * while key/value blocks travel round the group (Sec. 3.2, Sec. 4.3 communication cost).
  * This library is the work ONE rank does: a shard plan, one partial attention result per
  * ring step, the log-sum-exp merge of those partials, and the matching backward.
+ * Two forms of the device calls: the plain ones (fcp_attn_fwd_step, fcp_lse_merge, fcp_attn_bwd_step,
+ * fcp_grad_finalize) work one or several ring steps per call and combine across calls; the *_direct ones take a
+ * rank's whole work list at once and write every row that a single work item feeds - in a packed batch, most -
+ * in its final form straight from the attention kernel.
  *
  * Conventions
  *   - plain C ABI, no exceptions; every call returns 0 (FCP_OK) or a negative FCP_ERR_*;
