@@ -24,12 +24,14 @@
 //   * PING-PONG: waves w and w+4 share a SIMD (measured).  Matrix and vector instructions of
 //     DIFFERENT waves of a SIMD execute together almost perfectly, those of one wave hardly do.
 //     Each wave therefore alternates a matrix slot (scores of tile t, O += P V of tile t-1)
-//     with a vector slot (mask, maximum, exponentials, sum, conversion of tile t), and waves 4..7
-//     run one slot behind waves 0..3; a block barrier at every slot boundary keeps the two
-//     halves in opposite slots, so a SIMD's matrix pipe is busy in every slot;
+//     with a vector slot (fills of tile t+2, then mask, maximum, exponentials, sum, conversion of tile t), and
+//     waves 4..7 run one slot behind waves 0..3; a block barrier at every slot boundary keeps the two
+//     halves in opposite slots, so a SIMD's matrix pipe is busy in every slot.  A slot lasts as long as the matrix
+//     slot of the waves that are in it: nothing but the matrix instructions and their LDS reads is on that path;
+//   * direct mode: a tile whose rows no other work item of the launch covers stores its normalised O as bf16 and
+//     its LSE in their final places instead of a partial result;
 //   * key tiles completely below the diagonal skip the mask; key tiles completely above a
 //     wave's rows are not computed by that wave (it only keeps the barriers).
-#include <type_traits>
 
 #include "fcp_device.h"
 
