@@ -168,6 +168,8 @@ __device__ void build_list(
   __shared__ int32_t s_wave[kSchedThreads / 64];
   __shared__ int32_t s_hist[kBuckets];
   __shared__ int32_t s_max, s_rej, s_carry;
+  __shared__ int32_t s_off[kMaxExclusiveScan + 1];    // copy of item_off for short work lists: the tile decode below
+  const bool off_in_lds = n_work <= kMaxExclusiveScan;   // searches it, and a search in global memory is a chain of misses
   const int tid = threadIdx.x;
   if (tid == 0) { s_max = 0; s_rej = 0; s_carry = 0; }
   for (int b = tid; b < kBuckets; b += kSchedThreads) s_hist[b] = 0;
@@ -187,7 +189,10 @@ __device__ void build_list(
     int32_t total;
     const int32_t ex = block_exclusive_scan(cnt, s_wave, total);
     const int32_t carry = s_carry;
-    if (i < n_work) item_off[i] = carry + ex;
+    if (i < n_work) {
+      item_off[i] = carry + ex;
+      if (off_in_lds) s_off[i] = carry + ex;
+    }
     __syncthreads();
     if (tid == 0) s_carry = carry + total;
     __syncthreads();
@@ -217,10 +222,10 @@ __device__ void build_list(
     int32_t lo = 0, hi = n_work - 1;               // last item with item_off <= t
     while (lo < hi) {
       const int32_t mid = (lo + hi + 1) >> 1;
-      if (item_off[mid] <= t) lo = mid; else hi = mid - 1;
+      if ((off_in_lds ? s_off[mid] : item_off[mid]) <= t) lo = mid; else hi = mid - 1;
     }
     const fcp_work_desc w = work[lo];
-    const int32_t local = t - item_off[lo];
+    const int32_t local = t - (off_in_lds ? s_off[lo] : item_off[lo]);
     const int32_t row0_kv = cu[w.seq];
     const int32_t fl = item_flags[lo];
     for (int i = 0; i < 16; ++i) out.w[i] = 0;
@@ -259,9 +264,13 @@ __device__ void build_list(
     return bwd_cost(m, cu, w, sg, kt, tile, inner);
   };
 
+  // (a thread's first tile and its cost stay in registers for the scatter pass: with up to 1024 tiles, all of them)
+  Tile first_tile;
+  int32_t first_cost = 0;
   for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
     Tile tl;
     const int32_t c = decode(t, tl);
+    if (t == tid) { first_tile = tl; first_cost = c; }
     atomicAdd(&s_hist[min(c >> shift, kBuckets - 1)], 1);
   }
   __syncthreads();
@@ -279,7 +288,9 @@ __device__ void build_list(
   __syncthreads();
   for (int32_t t = tid; t < n_tiles; t += kSchedThreads) {
     Tile tl;
-    const int32_t c = decode(t, tl);
+    int32_t c;
+    if (t == tid) { tl = first_tile; c = first_cost; }
+    else c = decode(t, tl);
     const int32_t pos = atomicAdd(&s_hist[min(c >> shift, kBuckets - 1)], 1);
     tiles[pos] = tl;
   }
@@ -456,7 +467,10 @@ __global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
 
 static int row_state_blocks(int32_t tq, int32_t n_kv_rows) {
   int64_t blocks = ((int64_t)tq + n_kv_rows + kSchedThreads / 64 - 1) / (kSchedThreads / 64);
-  if (blocks > 512) blocks = 512;      // every block stages the whole work list first: few blocks, several rows per wave
+  // Every block stages the whole work list first, so few blocks with several rows per wave.  Measured on the 32K
+  // workload (forward / backward scheduling launch): 64 blocks 34 / 81 us, 128 blocks 28 / 50, 256 blocks - / 57,
+  // 512 blocks 41 / 58.
+  if (blocks > 128) blocks = 128;
   return blocks < 1 ? 1 : (int)blocks;
 }
 
