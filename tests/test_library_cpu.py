@@ -95,6 +95,19 @@ def test_device_entry_points_reject_bad_arguments_on_host():
     assert L.fcp_grad_finalize(fake, fake, -1, None) == B.FCP_ERR_INVALID_ARG
     assert L.fcp_scratch_bytes(B.FCP_SCRATCH_FWD, 1000, 1000, 4, 4, 128, 3, 2) > 64
     assert L.fcp_scratch_bytes(B.FCP_SCRATCH_BWD, 1000, 1000, 4, 4, 128, 3, 2) > 64
+    # the direct entry points: outputs are required, the mask tables go together, long work lists are refused
+    big = 1 << 30
+    assert L.fcp_attn_fwd_step_direct(fake, fake, fake, fake, 1, fake, 1, 1, 8, 8, 4, 4, 128, 0.1, None, fake, fake, None, fake, fake, big, None) == B.FCP_ERR_INVALID_ARG
+    assert L.fcp_attn_fwd_step_direct(fake, fake, fake, fake, 1, fake, 2000, 1, 8, 8, 4, 4, 128, 0.1, None, fake, fake, fake, fake, fake, big, None) == B.FCP_ERR_UNSUPPORTED
+    assert b"direct mode" in L.fcp_last_error()
+    assert L.fcp_lse_merge_direct(fake, fake, 1, 8, 8, 4, 128, fake, fake, None, 1, None) == B.FCP_ERR_INVALID_ARG
+    bwd = lambda **kw: L.fcp_attn_bwd_step_direct(fake, fake, fake, fake, fake, fake, fake, 1, fake, kw.get("n_work", 1), 8, 8, 4, 4, 128, 0.1,
+                                                 kw.get("q_limit"), None, fake, fake, fake, kw.get("dq_out", fake), fake, fake, fake, big, None)
+    assert bwd(dq_out=None) == B.FCP_ERR_INVALID_ARG
+    assert bwd(q_limit=fake) == B.FCP_ERR_INVALID_ARG and b"go together" in L.fcp_last_error()
+    assert bwd(n_work=2000) == B.FCP_ERR_UNSUPPORTED and b"direct mode" in L.fcp_last_error()
+    assert L.fcp_grad_finalize_direct(fake, fake, fake, fake, fake, None, fake, 1, 8, 8, 4, 4, 128, None) == B.FCP_ERR_INVALID_ARG
+    assert L.fcp_grad_finalize_direct(fake, fake, fake, fake, fake, fake, fake, 1, 8, 8, 4, 4, 96, None) == B.FCP_ERR_UNSUPPORTED
 
 
 def test_no_oracle_in_product_path():
