@@ -26,9 +26,11 @@ def bf16_tensor_to_f64(t):
     return synth.bf16_bits_to_f64(t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16))
 
 
-def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label="", spans=None, base_rank=None):
+def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label="", spans=None, base_rank=None,
+               direct=True):
     """Full element-by-element comparison of one rank (small workloads).  spans: full-attention spans
-    [(seq, start, len), ...] of a mixed mask, None = causal."""
+    [(seq, start, len), ...] of a mixed mask, None = causal.  direct=False: the work list is longer than the direct
+    entry points take; they must refuse it, and only the plain ones are compared."""
     import torch
     from paper_2602_21788_amd.rank import RankAttention
     ra = RankAttention(wl.seq_lens, wl.cp_degree, rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans,
@@ -53,6 +55,8 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
     assert res["LSE"] <= TOL_LSE_ABS, (label, res)
     # The direct forward (rows fed by one work item written once by the kernel, the others merged) on poisoned
     # buffers: the same bar, and the same values as partial results + merge up to the bf16 rounding of O.
+    if not direct:
+        return _plain_only(ra, wl, q, k, v, do, rows, O_ref, LSE_ref, sid, backward, res, label)
     for t in (ra.o, ra.lse, ra.o_part, ra.lse_part):
         t.fill_(float("nan"))
     ra.forward_direct()
@@ -108,4 +112,30 @@ def check_rank(wl, q, k, v, do, rank, backward=True, check_partials=False, label
             assert res[name + "_direct"] <= TOL_BF16_REL, (label, name, "direct", res)
             # against the accumulating path: the same arithmetic, except for the order of the fp32 atomics
             assert rel_err(direct[name], got[name]) <= 2.0 ** -7, (label, name, "direct vs accumulating")
+    return res
+
+
+def _plain_only(ra, wl, q, k, v, do, rows, O_ref, LSE_ref, sid, backward, res, label):
+    """Work lists beyond the direct entry points' limit: those refuse the list (and launch nothing), the plain
+    backward is compared with the oracle."""
+    import torch
+    import pytest
+    from paper_2602_21788_amd.binding import FcpError, FCP_ERR_UNSUPPORTED
+    with pytest.raises(FcpError) as ei:
+        ra.forward_steps_direct()
+    assert ei.value.code == FCP_ERR_UNSUPPORTED, label
+    if backward:
+        with pytest.raises(FcpError) as ei:
+            ra.backward_steps_direct()
+        assert ei.value.code == FCP_ERR_UNSUPPORTED, label
+        ra.backward()
+        torch.cuda.synchronize()
+        assert __import__("paper_2602_21788_amd").fcp_scratch_status(ra.scratch_b)[1] == 0, label
+        dQ_ref = oattn.attn_dq(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref, span_id=sid)
+        dK_ref, dV_ref = oattn.attn_dkv(q, k, v, do, wl.cu_seqlens, wl.softmax_scale, rows, O_ref, LSE_ref, span_id=sid)
+        for name, t, ref in (("dQ", ra.dq, dQ_ref), ("dK", ra.dk, dK_ref), ("dV", ra.dv, dV_ref)):
+            got = bf16_tensor_to_f64(t)
+            assert np.isfinite(got).all(), (label, name)
+            res[name] = rel_err(got, ref)
+            assert res[name] <= TOL_BF16_REL, (label, name, res)
     return res

@@ -83,7 +83,8 @@ def test_cfg2_full_size_sampled():
     """The 32K-token packed workload in the launch configuration bench.py times (rank 0, 32 query / 8 KV heads,
     D = 128).  The oracle cannot redo all of it in seconds, so: O, LSE and dQ of every 61st row of the rank for
     the query heads of KV heads 0 and 5, and dK, dV of those two KV heads in full (their query heads, every row
-    of the rank) - heads are independent, so a head subset is the exact result for those heads."""
+    of the rank) - heads are independent, so a head subset is the exact result for those heads.  Both the plain and
+    the direct entry points are held against the oracle on these samples."""
     import torch
     from paper_2602_21788_amd.rank import RankAttention
     from oracle import plan as oplan
@@ -118,8 +119,9 @@ def test_cfg2_full_size_sampled():
         t.fill_(float("nan"))
     ra.backward_direct()
     torch.cuda.synchronize()
+    direct = {}
     for name, acc, x in (("dQ", dQ, ra.dq), ("dK", dK, ra.dk), ("dV", dV, ra.dv)):
-        d = bf16_tensor_to_f64(x)
+        d = direct[name] = bf16_tensor_to_f64(x)
         assert np.isfinite(d).all(), name
         assert rel_err(d, acc) <= 2.0 ** -7, (name, "direct vs accumulating", rel_err(d, acc))
     G = wl.hq // wl.hkv
@@ -138,6 +140,12 @@ def test_cfg2_full_size_sampled():
              "dK": rel_err(dK[:, kvh:kvh + 1], dK_ref), "dV": rel_err(dV[:, kvh:kvh + 1], dV_ref)}
         _say(f"  kv head {kvh}: {e}")
         assert e["dK"] <= TOL_BF16_REL and e["dV"] <= TOL_BF16_REL
+        # the direct entry points (what bench.py times) against the oracle itself, the same samples
+        ed = {"O": rel_err(O_d[sel, hs], O_ref[sel]), "LSE": float(np.abs(LSE_d[sel, hs] - LSE_ref[sel]).max()),
+              "dQ": rel_err(direct["dQ"][sel, hs], dQ_ref), "dK": rel_err(direct["dK"][:, kvh:kvh + 1], dK_ref),
+              "dV": rel_err(direct["dV"][:, kvh:kvh + 1], dV_ref)}
+        _say(f"  kv head {kvh}, direct entry points: {ed}")
+        assert ed["LSE"] <= TOL_LSE_ABS and all(ed[n] <= TOL_BF16_REL for n in ("O", "dQ", "dK", "dV")), ed
 
 
 def test_planned_microbatch_atomic_groups_end_to_end():
