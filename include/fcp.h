@@ -122,6 +122,25 @@ int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t
                       void* scratch, size_t scratch_bytes, void* stream);
 
 /*
+ * fcp_attn_fwd_step_static -- fcp_attn_fwd_step for callers that cannot allocate device memory or carry a work
+ * area around: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * function, arguments, results and errors as fcp_attn_fwd_step, except that the scheduler's work area is a static
+ * device array inside the library (FCP_STATIC_SCRATCH_BYTES, held on every GPU the library runs on until the
+ * process ends) instead of `scratch`.  The call allocates nothing and frees nothing.
+ *   - a call that needs more than FCP_STATIC_SCRATCH_BYTES (see fcp_scratch_bytes(FCP_SCRATCH_FWD, ...)) returns
+ *     FCP_ERR_CAPACITY and launches nothing;
+ *   - every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two threads)
+ *     race and give undefined results; calls on one stream are ordered and safe.  Nothing has to be cleared between
+ *     calls;
+ *   - fcp_scratch_status has no access to the static area.
+ */
+#define FCP_STATIC_SCRATCH_BYTES (2 * 1024 * 1024)
+int fcp_attn_fwd_step_static(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                             int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                             int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                             float softmax_scale, float* o_part, float* lse_part, void* stream);
+
+/*
  * fcp_lse_merge -- combine the partials of the ring steps (online-softmax rescaling):
  *   LSE = ln sum_s exp(LSE_s),   O = sum_s exp(LSE_s - LSE) O_s.
  * A slot with LSE_s = -inf contributes nothing and its O rows are not read; a row whose

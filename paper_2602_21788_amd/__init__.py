@@ -9,4 +9,4 @@ from .binding import (CostModel, FcpError, fcp_attn_bwd_delta, fcp_attn_bwd_step
                       fcp_shard_plan, fcp_shard_plan_mixed, fcp_mask_tables, fcp_attn_fwd_step_mixed,
                       fcp_attn_bwd_step_mixed, fcp_group_shard_args, fcp_attn_fwd_step_running,
                       fcp_attn_bwd_step_direct, fcp_grad_finalize_direct, fcp_attn_fwd_step_direct,
-                      fcp_lse_merge_direct)
+                      fcp_lse_merge_direct, fcp_attn_fwd_step_static)

@@ -28,7 +28,7 @@ SPAN_DTYPE = np.dtype([("seq", "<i4"), ("start", "<i4"), ("len", "<i4")])
 EXPORTS = ["fcp_last_error", "fcp_shard_plan", "fcp_plan_groups", "fcp_scratch_bytes", "fcp_attn_fwd_step", "fcp_lse_merge",
            "fcp_attn_bwd_delta", "fcp_attn_bwd_step", "fcp_grad_finalize", "fcp_scratch_status",
            "fcp_group_shard_args", "fcp_attn_fwd_step_running", "fcp_shard_plan_mixed", "fcp_mask_tables", "fcp_attn_fwd_step_mixed", "fcp_attn_bwd_step_mixed",
-           "fcp_attn_bwd_step_direct", "fcp_grad_finalize_direct", "fcp_attn_fwd_step_direct", "fcp_lse_merge_direct"]
+           "fcp_attn_bwd_step_direct", "fcp_grad_finalize_direct", "fcp_attn_fwd_step_direct", "fcp_lse_merge_direct", "fcp_attn_fwd_step_static"]
 
 
 class FcpError(RuntimeError):
@@ -62,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.fcp_scratch_bytes.argtypes = [ctypes.c_int, I32, I32, I32, I32, I32, I64, I32]
         L.fcp_attn_fwd_step.restype = ctypes.c_int
         L.fcp_attn_fwd_step.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, I32, F, P, P, P, SZ, P]
+        L.fcp_attn_fwd_step_static.restype = ctypes.c_int
+        L.fcp_attn_fwd_step_static.argtypes = [P, P, P, P, I32, P, I64, I32, I32, I32, I32, I32, I32, F, P, P, P]
         L.fcp_lse_merge.restype = ctypes.c_int
         L.fcp_lse_merge.argtypes = [P, P, I32, I32, I32, I32, P, P, P]
         L.fcp_attn_bwd_delta.restype = ctypes.c_int
@@ -247,6 +249,16 @@ def fcp_attn_fwd_step(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, o_pa
                                    cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, n_parts, tq, tkv, hq, hkv, D,
                                    float(softmax_scale), _dev_ptr(o_part), _dev_ptr(lse_part), _dev_ptr(scratch),
                                    scratch.numel() * scratch.element_size(), _stream(stream)))
+
+
+def fcp_attn_fwd_step_static(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, o_part, lse_part, stream=None):
+    """fcp_attn_fwd_step with the library's static work area (no scratch argument, no allocation)."""
+    tq, hq, D = q.shape
+    tkv, hkv, _ = k.shape
+    n_work = work.numel() // WORK_DTYPE.itemsize
+    _check(lib().fcp_attn_fwd_step_static(_dev_ptr(q), _dev_ptr(k), _dev_ptr(v), _dev_ptr(cu_seqlens_kv),
+                                          cu_seqlens_kv.numel() - 1, _dev_ptr(work), n_work, n_parts, tq, tkv, hq, hkv, D,
+                                          float(softmax_scale), _dev_ptr(o_part), _dev_ptr(lse_part), _stream(stream)))
 
 
 def fcp_attn_fwd_step_mixed(q, k, v, cu_seqlens_kv, work, n_parts, softmax_scale, q_limit, o_part, lse_part, scratch,

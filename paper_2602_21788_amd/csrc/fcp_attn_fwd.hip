@@ -555,6 +555,47 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   return FCP_OK;
 }
 
+// ---- fcp_attn_fwd_step_static: the same call with the scheduler's work area in a static device array ----------
+// For callers that cannot allocate device memory.  The array below exists once per GPU the library runs on, for
+// the life of the process.  In host code its NAME is only a handle for the runtime: the device address comes from
+// hipGetSymbolAddress (once per device, with that device current) and only that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char fcp_static_scratch[FCP_STATIC_SCRATCH_BYTES];
+
+static int static_scratch_address(void** out) {
+  constexpr int kMaxDev = 64;
+  static std::atomic<void*> addr[kMaxDev];       // zero-initialised; one slot per device ordinal
+  int dev = 0;
+  FCP_HIP_CHECK(hipGetDevice(&dev));
+  void* p = (dev >= 0 && dev < kMaxDev) ? addr[dev].load(std::memory_order_acquire) : nullptr;
+  if (!p) {
+    FCP_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(fcp_static_scratch)));
+    if (!p) return fail(FCP_ERR_HIP, "fcp_attn_fwd_step_static: the static work area has no device address");
+    if (dev >= 0 && dev < kMaxDev) addr[dev].store(p, std::memory_order_release);   // (two threads store the same value)
+  }
+  *out = p;
+  return FCP_OK;
+}
+
+extern "C" int fcp_attn_fwd_step_static(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
+                                        int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
+                                        int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
+                                        float softmax_scale, float* o_part, float* lse_part, void* stream) {
+  fcp::clear_error();
+  if (tq < 0 || tkv < 1 || n_work < 0 || n_parts < 1 || hq < 1 || hkv < 1)
+    return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step_static: bad sizes");
+  const size_t need = fcp_scratch_bytes(FCP_SCRATCH_FWD, tq, tkv, hq, hkv, head_dim, n_work, n_parts);
+  if (need > (size_t)FCP_STATIC_SCRATCH_BYTES)
+    return fail(FCP_ERR_CAPACITY, "fcp_attn_fwd_step_static: this call needs a work area of %zu bytes, the static one has %zu "
+                                  "(use fcp_attn_fwd_step with a caller-owned scratch buffer)", need, (size_t)FCP_STATIC_SCRATCH_BYTES);
+  void* area = nullptr;
+  const int rc = static_scratch_address(&area);
+  if (rc != FCP_OK) return rc;
+  // every part of the area that the kernels read is written first by the scheduling launch of the same call (header,
+  // counters, offsets, flags, tile records), so what the previous call left needs no clearing
+  return fwd_step(q, k, v, cu_seqlens_kv, n_seqs, work, n_work, n_parts, tq, tkv, hq, hkv, head_dim, softmax_scale,
+                  nullptr, o_part, lse_part, area, (size_t)FCP_STATIC_SCRATCH_BYTES, stream);
+}
+
 extern "C" int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
                                  int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
                                  int32_t tq, int32_t tkv, int32_t hq, int32_t hkv, int32_t head_dim,
