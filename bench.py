@@ -11,9 +11,12 @@ with every input already resident in HBM.  The metric is causal-effective TFLOP/
 and head; masked pairs are not counted).  --mask mixed times the same path through the
 *_mixed entry points on the workload with synthetic image spans (not the headline number).
 
-Prints ONE JSON line (see the keys below); `roofline` is for the dominant kernel (the
-backward step), `cpu_baseline` times the fp64 CPU oracle on a bounded sample of the same
-workload.
+Prints ONE JSON line.  `value` / `ms_per_step` come from the wall clock around the K timed steps; every segment is
+also timed per step with events on the stream the kernels run on and reported as mean, median and min.  `roofline`
+is for the dominant launch (the backward step: its scheduling launch and the two attention kernels), `cpu_baseline`
+times the fp64 CPU oracle on a bounded sample of the same workload, and `secondary` (default run only) holds the
+other workloads, the CP-degree sweep and the merge on a bandwidth-sized input, a few steps each, device-side random
+inputs.
 """
 import argparse
 import json
@@ -32,6 +35,104 @@ PEAK_HBM_GBS = 8000.0
 # counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload only.
 MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "accumulate"): 5.66e9,
                               ("packed32k_lognormal24_h32x8_D128", "direct"): 4.65e9}
+SEGMENTS = ["fwd_step", "merge", "zero", "delta", "bwd_step", "finalize"]
+
+
+# ---- bookkeeping of a rank's share (algorithmic work; none of it is on the timed path) -------------------------------
+def rank_pairs(ra) -> int:
+    """Visible (query, key) pairs of the rank: sum over its rows of (position + 1), or of (last visible key
+    position + 1) under a mixed mask."""
+    if ra.spans is not None:
+        return int(ra.q_limit.astype(np.int64).sum()) + ra.tq
+    tot = 0
+    for c in ra.my_chunks:
+        a, n = int(c["seq_start"]), int(c["len"])
+        tot += n * a + n * (n + 1) // 2
+    return tot
+
+
+def merge_bytes(ra, direct: bool) -> int:
+    """Algorithmic bytes of the merge: per row and head, each contributing slot is read once (D fp32 + its LSE),
+    every slot's LSE is read, and O (bf16) + LSE are written.  direct: fcp_lse_merge_direct skips the rows that
+    exactly one work item feeds (one state byte per row is read)."""
+    parts_per_row = np.zeros(ra.tq, np.int64)
+    for w in ra.work:
+        parts_per_row[int(w["q_local_off"]):int(w["q_local_off"]) + int(w["q_len"])] += 1
+    D = ra.D
+    if direct:
+        merged = parts_per_row != 1
+        return int(ra.hq * (parts_per_row[merged].sum() * (D * 4) + merged.sum() * (ra.n_parts * 4 + D * 2 + 4)) + ra.tq * ra.hq)
+    return int(ra.hq * (parts_per_row.sum() * (D * 4) + ra.tq * (ra.n_parts * 4 + D * 2 + 4)))
+
+
+def stats(xs):
+    xs = np.asarray(xs, np.float64)
+    return {"mean": float(xs.mean()), "median": float(np.median(xs)), "min": float(xs.min())}
+
+
+def timed_steps(ra, steps, warmup, forward="direct", backward="direct"):
+    """W warm-up steps, then K timed ones.  Returns (wall ms per step, {segment: [ms per step]})."""
+    import torch
+
+    def step(events=None):
+        def mark(i):
+            if events is not None:
+                events[i].record()
+        if forward == "running":
+            mark(0); ra.forward_running()
+            mark(1)
+        elif forward == "direct":
+            mark(0); ra.forward_steps_direct()
+            mark(1); ra.merge_direct()
+        else:
+            mark(0); ra.forward_steps()
+            mark(1); ra.merge()
+        if backward == "direct":
+            mark(2)
+            mark(3); ra.backward_delta()
+            mark(4); ra.backward_steps_direct()
+            mark(5); ra.finalize_direct()
+        else:
+            mark(2); ra.zero_grads()
+            mark(3); ra.backward_delta()
+            mark(4); ra.backward_steps()
+            mark(5); ra.finalize()
+        mark(6)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    seg = {n: [evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(steps)] for i, n in enumerate(SEGMENTS)}
+    seg["step"] = [evs[s][0].elapsed_time(evs[s][6]) for s in range(steps)]
+    import paper_2602_21788_amd as fcp
+    assert fcp.fcp_scratch_status(ra.scratch_f)[1] == 0 and fcp.fcp_scratch_status(ra.scratch_b)[1] == 0
+    return (t1 - t0) * 1e3 / steps, seg
+
+
+def rates(ra, seg, pairs, forward, backward):
+    """Per-segment times (mean / median / min over the timed steps) and the rates that follow from the medians."""
+    fl = float(pairs) * ra.D * ra.hq
+    st = {n: stats(seg[n]) for n in seg}
+    f, b, m = st["fwd_step"]["median"], st["bwd_step"]["median"], st["merge"]["median"]
+    whole_bwd = float(np.median(np.asarray(seg["zero"]) + np.asarray(seg["delta"]) + np.asarray(seg["bwd_step"]) +
+                                np.asarray(seg["finalize"])))
+    mb = merge_bytes(ra, forward == "direct")
+    return {
+        "fwd_step": {"ms": st["fwd_step"], "tflops": 4 * fl / f / 1e9, "frac_mfma_peak": 4 * fl / f / 1e9 / PEAK_BF16_TFLOPS},
+        "bwd_step": {"ms": st["bwd_step"], "tflops": 10 * fl / b / 1e9, "frac_mfma_peak": 10 * fl / b / 1e9 / PEAK_BF16_TFLOPS},
+        "bwd_whole": {"ms": whole_bwd, "tflops": 10 * fl / whole_bwd / 1e9, "frac_mfma_peak": 10 * fl / whole_bwd / 1e9 / PEAK_BF16_TFLOPS,
+                      "covers": "zero + delta + bwd_step + finalize"},
+        "merge": {"ms": st["merge"], "bytes": mb, "gbs": mb / m / 1e6, "frac_hbm_peak": mb / m / 1e6 / PEAK_HBM_GBS},
+        "delta": {"ms": st["delta"]}, "zero": {"ms": st["zero"]}, "finalize": {"ms": st["finalize"]},
+        "step": {"ms": st["step"], "tflops": 14 * fl / st["step"]["median"] / 1e9},
+    }
 
 
 def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30, spans=None):
@@ -66,37 +167,54 @@ def cpu_baseline(wl, q, k, v, do, rows, budget_rows=1 << 30, spans=None):
 
 def degree_sweep(steps, warmup):
     """One 32768-token sequence at CP degrees 1..8: what rank 0 does per layer (all ring steps of its two zigzag
-    chunks, merge, backward), device-side random inputs."""
+    chunks, merge, backward) through the plain entry points, device-side random inputs; medians."""
     import torch
     from paper_2602_21788_amd.rank import RankAttention
     rows = []
     for d in range(1, 9):
         ra = RankAttention([32768], [d], 0, 32, 8, 128)
         ra.set_random_inputs(seed=d)
-        pairs = ra.pairs()
-        for _ in range(warmup):
-            ra.forward(); ra.backward()
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-        tf, tm, tb = [], [], []
-        for _ in range(steps):
-            ev[0].record(); ra.forward_steps(); ev[1].record(); ra.merge(); ev[2].record()
-            ra.zero_grads(); ra.backward_delta(); torch.cuda.synchronize()
-            ev[0].synchronize()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(); ra.backward_steps(); b.record(); torch.cuda.synchronize()
-            tf.append(ev[0].elapsed_time(ev[1])); tm.append(ev[1].elapsed_time(ev[2])); tb.append(a.elapsed_time(b))
-        f, m, b = float(np.median(tf)), float(np.median(tm)), float(np.median(tb))
-        fl = pairs * 128.0 * 32.0
+        pairs = rank_pairs(ra)
+        _, seg = timed_steps(ra, steps, warmup, "partial", "accumulate")
+        r = rates(ra, seg, pairs, "partial", "accumulate")
         rows.append({"degree": d, "rank": 0, "rank_rows": ra.tq, "pairs": pairs, "n_parts": ra.n_parts,
-                     "fwd_step_ms": f, "merge_ms": m, "bwd_step_ms": b,
-                     "fwd_tflops": 4.0 * fl / (f * 1e-3) / 1e12, "bwd_tflops": 10.0 * fl / (b * 1e-3) / 1e12,
-                     "fwd_frac_mfma_peak": 4.0 * fl / (f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                     "bwd_frac_mfma_peak": 10.0 * fl / (b * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+                     "fwd_step_ms": r["fwd_step"]["ms"]["median"], "merge_ms": r["merge"]["ms"]["median"],
+                     "bwd_step_ms": r["bwd_step"]["ms"]["median"],
+                     "fwd_tflops": r["fwd_step"]["tflops"], "bwd_tflops": r["bwd_step"]["tflops"],
+                     "fwd_frac_mfma_peak": r["fwd_step"]["frac_mfma_peak"], "bwd_frac_mfma_peak": r["bwd_step"]["frac_mfma_peak"],
+                     "merge_gbs": r["merge"]["gbs"]})
         del ra
         torch.cuda.empty_cache()
-    return {"metric": "rank-local varlen causal attn TFLOP/s, CP degree sweep on one 32768-token sequence",
-            "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": "L32768_d1to8_h32x8_D128", "rank": 0}, "sweep": rows}
+    return rows
+
+
+def secondary(steps, warmup):
+    """The other workloads (rank of the workload table, direct entry points), the plain-path merge of the 131072-token
+    workload (1.9 GB of partial results: the merge's bandwidth figure), and the degree sweep."""
+    import torch
+    import fcp_synth as synth
+    from paper_2602_21788_amd.rank import RankAttention
+    out = {"steps": steps, "warmup": warmup, "inputs": "device-side N(0,1) bf16", "timing": "median over the timed steps",
+           "workloads": {}}
+    for cfg in (1, 3, 4):
+        wl = synth.make_workload(cfg)
+        ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale)
+        ra.set_random_inputs(seed=cfg)
+        pairs = rank_pairs(ra)
+        wall, seg = timed_steps(ra, steps, warmup)
+        r = rates(ra, seg, pairs, "direct", "direct")
+        entry = {"rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "n_parts": ra.n_parts, "ms_per_step_wall": wall,
+                 "tflops": 14.0 * pairs * wl.head_dim * wl.hq / (wall * 1e-3) / 1e12, "kernels": r}
+        if cfg == 3:
+            _, seg_p = timed_steps(ra, steps, warmup, "partial", "direct")
+            rp = rates(ra, seg_p, pairs, "partial", "direct")
+            entry["merge_plain"] = rp["merge"]
+            entry["merge_plain"]["note"] = "fcp_lse_merge over every row of the rank: the merge's HBM figure"
+        out["workloads"][wl.name] = entry
+        del ra
+        torch.cuda.empty_cache()
+    out["degree_sweep_L32768_h32x8_D128_rank0_plain_entry_points"] = degree_sweep(steps, warmup)
+    return out
 
 
 def main():
@@ -117,9 +235,9 @@ def main():
                     help="direct (default): fcp_attn_bwd_step_direct + fcp_grad_finalize_direct - rows whose whole "
                          "gradient comes from one unit of work are written as bf16 by their kernel, nothing is cleared "
                          "beforehand; accumulate: clear the fp32 accumulators, fcp_attn_bwd_step, convert all of them")
-    ap.add_argument("--degree-sweep", action="store_true",
-                    help="secondary table instead of the benchmark line: one 32768-token sequence at CP degrees 1..8 "
-                         "(rank 0's share, 32 / 8 heads, D = 128), forward and backward step times and rates")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="leave out the secondary measurements (other workloads, merge at size, degree sweep)")
+    ap.add_argument("--secondary-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy after the timed steps: the reference dispatch for scaling "
@@ -138,85 +256,38 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    if args.degree_sweep:
-        print(json.dumps(degree_sweep(args.steps, args.warmup)))
-        return
     wl = synth.make_workload(args.workload)
     q, k, v, do = synth.draw_qkvdo(wl)
     spans = synth.image_spans(wl.seq_lens, wl.seed) if args.mask == "mixed" else None
     ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
     ra.set_inputs(q, k, v, do)
     wl_name = wl.name + ("_img576" if spans is not None else "")
-    pairs = ra.pairs()
-    flops_fwd = 4.0 * pairs * wl.head_dim * wl.hq
-    flops_bwd = 10.0 * pairs * wl.head_dim * wl.hq
+    pairs = rank_pairs(ra)
+    flops = 14.0 * pairs * wl.head_dim * wl.hq
 
-    names = ["fwd_step", "merge", "zero", "delta", "bwd_step", "finalize"]
-
-    def step(events=None):
-        def mark(i):
-            if events is not None:
-                events[i].record()
-        if args.forward == "running":
-            mark(0); ra.forward_running()
-            mark(1)
-        elif args.forward == "direct":
-            mark(0); ra.forward_steps_direct()
-            mark(1); ra.merge_direct()
-        else:
-            mark(0); ra.forward_steps()
-            mark(1); ra.merge()
-        if args.backward == "direct":
-            mark(2)
-            mark(3); ra.backward_delta()
-            mark(4); ra.backward_steps_direct()
-            mark(5); ra.finalize_direct()
-        else:
-            mark(2); ra.zero_grads()
-            mark(3); ra.backward_delta()
-            mark(4); ra.backward_steps()
-            mark(5); ra.finalize()
-        mark(6)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        step(evs[s])
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    seg_ms = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
-              for i, n in enumerate(names)}
-
-    import paper_2602_21788_amd as fcp
-    assert fcp.fcp_scratch_status(ra.scratch_f)[1] == 0 and fcp.fcp_scratch_status(ra.scratch_b)[1] == 0
-
-    value = (flops_fwd + flops_bwd) / (ms_per_step * 1e-3) / 1e12
-    bwd_tflops = flops_bwd / (seg_ms["bwd_step"] * 1e-3) / 1e12
-    fwd_tflops = flops_fwd / (seg_ms["fwd_step"] * 1e-3) / 1e12
-    merge_gbs = ra.merge_bytes(direct=args.forward == "direct") / (seg_ms["merge"] * 1e-3) / 1e9
+    ms_per_step, seg = timed_steps(ra, args.steps, args.warmup, args.forward, args.backward)
+    kern = rates(ra, seg, pairs, args.forward, args.backward)
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    # roofline of the dominant launch: algorithmic flops of one backward step over the AVERAGE duration of the launch
+    bwd_mean_ms = kern["bwd_step"]["ms"]["mean"]
+    bwd_tflops = 10.0 * pairs * wl.head_dim * wl.hq / (bwd_mean_ms * 1e-3) / 1e12
+    default_line = args.workload == 2 and args.mask == "causal" and args.forward == "direct" and args.backward == "direct"
     out = {
         "metric": "rank-local varlen causal attn TFLOP/s fwd+bwd, % of MFMA bf16 peak",
         "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": kern["step"]["ms"]["median"], "ms_per_step_min": kern["step"]["ms"]["min"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl_name, "mask": args.mask, "forward": args.forward, "backward": args.backward, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
                    "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
                    "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
                    "seed": wl.seed},
-        "roofline": {"bound": "mfma", "kernel": f"{'fcp_attn_bwd_step_direct' if args.backward == 'direct' else 'fcp_attn_bwd_step'} (dkv_kernel<{wl.head_dim}> + dq_kernel<{wl.head_dim}>)",
+        "roofline": {"bound": "mfma", "kernel": f"{'fcp_attn_bwd_step_direct' if args.backward == 'direct' else 'fcp_attn_bwd_step'} (scheduling launch + dkv_kernel<{wl.head_dim}> + dq_kernel<{wl.head_dim}>)",
                      "achieved": bwd_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get((wl_name, args.backward))},
-        "kernels": {
-            "fwd_step": {"ms": seg_ms["fwd_step"], "tflops": fwd_tflops, "frac_mfma_peak": fwd_tflops / PEAK_BF16_TFLOPS},
-            "bwd_step": {"ms": seg_ms["bwd_step"], "tflops": bwd_tflops, "frac_mfma_peak": bwd_tflops / PEAK_BF16_TFLOPS},
-            "merge": {"ms": seg_ms["merge"], "gbs": merge_gbs, "frac_hbm_peak": merge_gbs / PEAK_HBM_GBS},
-            "delta": {"ms": seg_ms["delta"]}, "zero": {"ms": seg_ms["zero"]}, "finalize": {"ms": seg_ms["finalize"]},
-        },
+                     "frac": bwd_tflops / PEAK_BF16_TFLOPS, "traffic": MEASURED_BWD_TRAFFIC_BYTES.get((wl_name, args.backward)),
+                     "frac_whole_backward": kern["bwd_whole"]["frac_mfma_peak"],
+                     "frac_forward_step": kern["fwd_step"]["frac_mfma_peak"]},
+        "kernels": kern,
     }
     if args.copy_calibration:
         src = torch.full((1 << 28,), 1.0, dtype=torch.float32, device="cuda")
@@ -225,8 +296,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    rows = ra.rows
+    del ra
+    torch.cuda.empty_cache()
+    if default_line and not args.no_secondary:
+        out["secondary"] = secondary(args.secondary_steps, 3)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, do, ra.rows, spans=spans)
+        out["cpu_baseline"] = cpu_baseline(wl, q, k, v, do, rows, spans=spans)
     print(json.dumps(out))
 
 

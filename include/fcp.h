@@ -114,6 +114,9 @@ size_t fcp_scratch_bytes(int which, int32_t tq, int32_t tkv, int32_t hq, int32_t
  * Items are checked on the device against tq, tkv, n_seqs and n_parts; an item that fails is
  * skipped and counted (see fcp_scratch_status); no access leaves the given extents.
  * Two items that cover the same (row, step) are a caller error (last writer wins).
+ * Limits: n_work <= 2^24 items (FCP_ERR_UNSUPPORTED beyond); a key segment of an item at most 2^30 bytes of pool
+ * rows (2^30 / (hkv * head_dim * 2) keys; longer segments are rejected on the device and counted); the CP degree
+ * itself is not limited (any integer, Sec. 4.2) beyond n_parts partial slots of memory.
  */
 int fcp_attn_fwd_step(const void* q, const void* k, const void* v, const int32_t* cu_seqlens_kv,
                       int32_t n_seqs, const fcp_work_desc* work, int64_t n_work, int32_t n_parts,
@@ -146,6 +149,8 @@ int fcp_attn_fwd_step_static(const void* q, const void* k, const void* v, const 
  * A slot with LSE_s = -inf contributes nothing and its O rows are not read; a row whose
  * slots are all -inf gets O = 0, LSE = -inf.  o [tq,hq,D] bf16 (round to nearest even),
  * lse [hq,tq] fp32.  All pointers device.
+ * Limit: n_parts <= 16 per call (FCP_ERR_UNSUPPORTED beyond) - a ring of more than 16 steps merges in rounds, the
+ * result of a round being one more partial (the merge is associative), or uses fcp_attn_fwd_step_running.
  */
 int fcp_lse_merge(const float* o_part, const float* lse_part, int32_t n_parts, int32_t tq,
                   int32_t hq, int32_t head_dim, void* o, float* lse, void* stream);
@@ -185,7 +190,7 @@ int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, i
  * [tkv,hkv,D].  Rows (keys) that only one work item of the call touches are read, added to and
  * written back with plain loads and stores; the others use fp32 atomics, so their summation
  * order varies run to run.  While the call runs nobody else may write the accumulators.
- * Limits: tq*hq*head_dim*2 and tkv*hkv*head_dim*2 below 2^31 bytes (FCP_ERR_UNSUPPORTED).
+ * Limits: tq*hq*head_dim and tkv*hkv*head_dim below 2^29 elements, n_work <= 2^24 items (FCP_ERR_UNSUPPORTED).
  * Other arguments as in fcp_attn_fwd_step; scratch sized with FCP_SCRATCH_BWD.
  */
 int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d_o,

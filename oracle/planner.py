@@ -13,7 +13,7 @@ at odds with itself:
     Each sequence goes into the open bin with the LEAST headroom that still holds it (ties: the bin opened
     first); if none holds it a new bin opens with d_min = ceil(|s| / cap) and capacity d_min * cap.
   * time of a group at degree d (Eq. 8-10).  Eq. 8 as printed has no d, yet Eq. 11 needs T(G, d) and CP
-    "partitions each sequence evenly into d chunks" (Sec. 4.3), so the compute terms are divided by d:
+    splits every sequence evenly over the d ranks of its group (Sec. 4.3), so the compute terms are divided by d:
         T_cpa = sum_k alpha1 (1 + eta_k) |s_k|^2 / d          (attention compute)
         T_cp  = T_cpa + sum_k alpha2 |s_k| / d + beta1
         T_cm  = 0 for d = 1, else sum_k alpha3 |s_k| / v + beta2   (Eq. 9; no ring, no exchange)

@@ -40,7 +40,7 @@ def _stale(out: str, deps) -> bool:
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     hipcc = _hipcc()
-    flags = FLAGS + os.environ.get("FCP_EXTRA_FLAGS", "").split()   # e.g. -DFCP_TIMING for development builds
+    flags = FLAGS
     jobs = []
     for src in SOURCES:
         sp = os.path.join(CSRC, src)

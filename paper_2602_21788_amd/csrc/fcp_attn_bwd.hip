@@ -33,7 +33,7 @@ namespace {
 template <int D>
 struct DqCfg {
   static constexpr int BM = kDqBM;                 // 128 query rows per unit (32 per P / dS wave)
-  static constexpr int BK = 32;                    // keys per step
+  static constexpr int BK = kDqBN;                 // keys per step
   static constexpr int NWAVE = 12;
   using DT = DualTile<D>;
   static constexpr int TILE = DT::bytes(BK);       // one K or V block
@@ -91,11 +91,7 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
   unsigned char* const xg = smem + C::XOFF + pw * C::XGROUP + lane * 16;
   unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
   unsigned char* const x_ds = xg + 2 * C::PB;
-
-  PhaseTimer pt;
-  pt.begin();
   for (;;) {
-    pt.mark(0);
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
     const QTile t = read_record<QTile, 12>(s_rec);
@@ -221,7 +217,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         }
       };
       if (role == 0) {
-        pt.mark(1);
         for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
           wait_fills();
           __syncthreads();
@@ -252,7 +247,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 #pragma unroll
           for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_pb + (it & 1) * C::PB + j * 1024) = pb[j];
         }
-        pt.mark(2);
       } else {
         bool prev_active = false;
         f32x16 dpacc = zero16();   // dP^T - delta of step it - 1 at the top of iteration it
@@ -342,7 +336,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
       constexpr int lag = 2;
       const unsigned char* const xb = smem + C::XOFF + (2 * qp) * C::XGROUP + lane * 16 + 2 * C::PB;   // dS^T of group 2 qp + kb
       const unsigned char* lstage = smem + (C::NSTAGE - lag) * C::STAGE;      // the stage of step it - lag
-      pt.mark(1);
       for (int it = 0; it < n_iter + 2; ++it, lstage = next_stage(lstage)) {
         wait_fills();
         __syncthreads();
@@ -383,7 +376,6 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
             __builtin_amdgcn_sched_barrier(0);
           }
       }
-      pt.mark(2);
       // epilogue: dQ [query x channel] * scale -> accumulator rows (or, in direct mode, the final bf16 rows: half a
       // line per store)
       if (direct) {
@@ -415,11 +407,8 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
             }
       }
     }
-    pt.mark(3);
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
-    pt.mark(4);
   }
-  pt.end(p.hdr);
 }
 
 }  // namespace
@@ -454,8 +443,9 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   const size_t need = fcp_scratch_bytes(FCP_SCRATCH_BWD, tq, tkv, hq, hkv, head_dim, n_work, 1);
   if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_bwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
 
-  if ((int64_t)tq * hq * head_dim * 2 >= ((int64_t)1 << 31) || (int64_t)tkv * hkv * head_dim * 2 >= ((int64_t)1 << 31))
-    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim * 2 and tkv * hkv * head_dim * 2 must stay below 2^31 bytes");
+  // (32-bit byte offsets into Q / dO / dQ and the pool, advanced a few blocks past the end by the fills)
+  if ((int64_t)tq * hq * head_dim * 4 >= ((int64_t)1 << 31) || (int64_t)tkv * hkv * head_dim * 4 >= ((int64_t)1 << 31))
+    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim and tkv * hkv * head_dim must stay below 2^29 elements");
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap_kv = fcp::kv_tile_cap(tkv, n_work);
   const int64_t cap_q = fcp::q_tile_cap(tq, tkv, n_work, 1 << 20);

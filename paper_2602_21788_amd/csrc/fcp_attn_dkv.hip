@@ -103,9 +103,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
   unsigned char* const xg = smem + C::XOFF + pw * C::XGROUP + lane * 16;
   unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
   unsigned char* const x_ds = xg + 2 * C::PB;
-
-  PhaseTimer pt;
-  pt.begin();
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
@@ -234,10 +231,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       };
       if (role == 0) {
         for (int it = 0; it < n_iter + C::DRAIN; ++it, stage = next_stage(stage)) {
-          pt.mark(0);
           wait_fills();
           __syncthreads();
-          pt.mark(1);
           fill_next();
           const int jb = j;
           next_block();
@@ -248,7 +243,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           for (int j = 0; j < 4; ++j) nl[j] = *reinterpret_cast<const f32x4*>(stat + 8 * j);
           f32x16 sacc = zero16();
           contract(sacc, stage);
-          pt.mark(2);
           // P = exp2(c S - LSE log2 e) with the mask.  Rows past the item's last row need no mask: their Q, dO
           // and statistics arrive as zeros, so P = 1 there meets dO = 0 in dV and dP - delta = 0 in dS.  That
           // leaves the causal edge and the keys past the tile's last.
@@ -273,16 +267,13 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
           for (int i = 0; i < 16; ++i) pb[i / 8][i % 8] = (__bf16)pr[i / 4][i % 4];
 #pragma unroll
           for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_pb + (it & 1) * C::PB + j * 1024) = pb[j];
-          pt.mark(3);
         }
       } else {
         bool prev_active = false;
         f32x16 dpacc = zero16();   // dP - delta of step it - 1 at the top of iteration it
         for (int it = 0; it < n_iter + C::DRAIN; ++it, stage = next_stage(stage)) {
-          pt.mark(0);
           wait_fills();
           __syncthreads();
-          pt.mark(1);
           fill_next();
           const bool active = it < n_iter && j >= j_act;
           next_block();
@@ -297,7 +288,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_ds + ((it - 1) & 1) * C::PB + j * 1024) = dsb[j];
           }
-          pt.mark(2);
           if (active) {
             const float* stat = reinterpret_cast<const float*>(stage + 2 * C::TILE) + C::SLOT / 4 + 4 * g2;
 #pragma unroll
@@ -308,7 +298,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
             }
             contract(dpacc, stage + C::TILE);
           }
-          pt.mark(3);
           prev_active = active;
         }
       }
@@ -385,12 +374,10 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
       bf16x8 bop[2][2] = {}, fr[N] = {};                           // operands of the step of the next iteration
       bool have = false, act0 = false, act1 = false;
       for (int it = 0; it < n_iter + C::DRAIN; ++it, lstage = next_stage(lstage)) {
-        pt.mark(0);
         // the requests of the last iteration have been served: their sources may be overwritten after the barrier
         __builtin_amdgcn_s_waitcnt(0xC07F);
         wait_fills();
         __syncthreads();
-        pt.mark(1);
         fill_next();
         if (have) {
           // acc += P^T dO (dS^T Q): k-step tt of a P (dS) operand covers block rows 16 tt .. 16 tt + 15.  A group that
@@ -411,7 +398,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
               __builtin_amdgcn_sched_barrier(0);
             }
         }
-        pt.mark(2);
         // requests for step s1 = it + 1 - lag: P of step s1 was written in iteration s1 <= it - 1 and dS of step s1 in
         // iteration s1 + 1 <= it - 1, so both are visible since this iteration's barrier
         const int s1 = it + 1 - lag;
@@ -439,7 +425,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
             fr[x] = tr_read_8(b0 + traddr[0][x % C::NVA], b0 + traddr[1][x % C::NVA]);
           }
         }
-        pt.mark(3);
       }
       // epilogue: dV or dK [key x channel] -> pool accumulators (or, in direct mode, the final bf16 rows: half a line
       // per store)
@@ -474,7 +459,6 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
     }
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }
-  pt.end(p.hdr);
 }
 
 }  // namespace

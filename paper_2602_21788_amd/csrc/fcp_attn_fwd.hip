@@ -129,9 +129,6 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
 #pragma unroll
     for (int db = 0; db < C::NVA; ++db) vaddr[db] = C::KBYTES + tile_off<VT>(row0, 4 * db + chunk0) + 8 * (lane & 1);
   }
-
-  PhaseTimer pt;
-  pt.begin();
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
@@ -399,8 +396,6 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     __syncthreads();                       // tiles 0 and 1 have landed
     if (grp == 1) __syncthreads();
     for (int it = 0; it <= n_iter; ++it) {
-      pt.mark(0);
-      pt.mark(1);
       const bool do_s = it < n_w, do_pv = it > 0 && it - 1 < n_w;
       // the matrix stream goes first at the SIMD's issue port: an MFMA is wanted every 32 cycles and must not
       // queue behind the partner wave's vector instructions
@@ -409,15 +404,12 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       if (do_s) score_part(it);
       if (do_pv) pv_part(it);
       __builtin_amdgcn_s_setprio(0);
-      pt.mark(2);
       // slot boundary: this wave's fills (issued a step ago) have landed, then everybody meets
       __builtin_amdgcn_s_waitcnt(kWaitVm0);
       __syncthreads();
       fill_next();
       if (do_s) vector_slot(it);
-      pt.mark(3);
       __syncthreads();
-      pt.mark(4);
     }
     if (grp == 0) __syncthreads();
 
@@ -469,7 +461,6 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     }
     uq.advance(&s_next_unit, s_rec);   // hand the next unit to the block (barrier: LDS stages are free)
   }
-  pt.end(p.hdr);
 }
 
 }  // namespace
@@ -497,7 +488,7 @@ static int fwd_step(const void* q, const void* k, const void* v, const int32_t* 
   const uintptr_t align_mask = reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k) |
                                reinterpret_cast<uintptr_t>(v) | reinterpret_cast<uintptr_t>(o_part);
   if (align_mask & 15u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: q/k/v/o_part must be 16-byte aligned");
-  if (reinterpret_cast<uintptr_t>(scratch) & 63u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: scratch must be 64-byte aligned");
+  if (reinterpret_cast<uintptr_t>(scratch) & 255u) return fail(FCP_ERR_INVALID_ARG, "fcp_attn_fwd_step: scratch must be 256-byte aligned");
   const size_t need = fcp_scratch_bytes(FCP_SCRATCH_FWD, tq, tkv, hq, hkv, head_dim, n_work, n_parts);
   if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_fwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
   if ((int64_t)tq * hq * head_dim * (int64_t)n_parts > ((int64_t)1 << 40))

@@ -151,35 +151,6 @@ __device__ inline int fill_voff(int rpw, int wave, int i, int lane, int row_byte
   return row * row_bytes + (((lane % T::CPR) ^ T::key(row)) << 4);
 }
 
-// Development aid (compiled in with -DFCP_TIMING=<wave>): that wave of every block accumulates the shader
-// cycles between consecutive marks i-1 -> i (i = 1..4) and adds them, in units of 16 cycles, to the four spare
-// words of the schedule header at kernel end (word pad0: whole kernel, units of 256 cycles).
-#ifdef FCP_TIMING
-struct PhaseTimer {
-  long long acc[4] = {0, 0, 0, 0}, last = 0, start = 0;
-  __device__ void begin() { start = __builtin_readcyclecounter(); }
-  __device__ void mark(int i) {
-    if (threadIdx.x == FCP_TIMING * 64) {
-      const long long now = __builtin_readcyclecounter();
-      if (i > 0) acc[i - 1] += now - last;
-      last = now;
-    }
-  }
-  __device__ void end(SchedHeader* hdr) {
-    if (threadIdx.x == FCP_TIMING * 64) {
-      for (int i = 0; i < 4; ++i) atomicAdd(&hdr->pad1[i], (int32_t)(acc[i] >> 4));
-      atomicAdd(&hdr->pad0, (int32_t)((__builtin_readcyclecounter() - start) >> 8));
-    }
-  }
-};
-#else
-struct PhaseTimer {
-  __device__ void begin() {}
-  __device__ void mark(int) {}
-  __device__ void end(SchedHeader*) {}
-};
-#endif
-
 // Unit queue of a persistent block.  Units are numbered per XCD counter; unit u of an XCD is
 // (tile u / per_tile, sub-index u % per_tile).  Wave 0 keeps the atomic for the unit after next
 // and the 64-byte record of the next unit in flight while the block computes the current one,

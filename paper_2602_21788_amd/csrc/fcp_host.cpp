@@ -65,8 +65,8 @@ int build_span_index(const char* who, const int32_t* seq_lens, int32_t n_seqs, c
 
 }  // namespace
 
-// Zigzag shard plan.  The paper fixes only "split evenly over the d ranks" (Sec. 4.3) and
-// "d is any positive integer" (Sec. 4.2); the 2d-chunk zigzag with the remainder spread over
+// Zigzag shard plan.  The paper fixes only an even split of every sequence over the d ranks of its group (Sec. 4.3)
+// and that d may be any positive integer (Sec. 4.2); the 2d-chunk zigzag with the remainder spread over
 // the first chunks is the load-balanced form of that split for a causal mask.  With full-attention
 // spans (Sec. 4.3, time estimation) the chunks stay the same and a query chunk additionally gets the
 // later key chunks that a span reaching over the chunk border makes visible.

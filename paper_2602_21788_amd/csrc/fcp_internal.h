@@ -77,10 +77,15 @@ struct Tile { int32_t w[16]; };  // storage type of the list
 constexpr int kFwdBM = 256;      // query rows per forward unit
 constexpr int kFwdBN = 64;       // keys per forward inner step
 constexpr int kDqBM = 128;       // query rows per dQ unit
-constexpr int kDqBN = 64;        // keys per dQ inner step
+constexpr int kDqBN = 32;        // keys per dQ inner step
 constexpr int kBwdBN = 128;      // keys per dK/dV unit
 constexpr int kBwdBM = 32;       // query rows per dK/dV inner step
 constexpr int kMinQTile = 128;   // smallest query tile of any kernel (sizes the tile lists)
+
+// Longest key segment of a work item the kernels take.  Byte offsets into a segment travel in 32-bit scalar
+// offsets of buffer instructions, and the fills run a few tiles past a segment's end (those land outside the
+// resource's range and read as zero): with a segment below 2^30 bytes the offsets stay far from 2^31.
+inline int32_t max_segment_keys(int64_t kv_row_bytes) { return (int32_t)(((int64_t)1 << 30) / kv_row_bytes); }
 
 // Upper bounds on the number of tiles of a valid plan (anything beyond is dropped and
 // counted as rejected).  Query tiles: every (row, slot) belongs to at most one item, and over

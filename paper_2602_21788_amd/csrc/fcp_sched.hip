@@ -497,7 +497,7 @@ int launch_row_states(int64_t kv_row_bytes, const RowStates& rs, const int32_t* 
   int rc = check_row_states(n_work);
   if (rc != FCP_OK) return rc;
   hipLaunchKernelGGL(row_state_kernel, dim3((unsigned)row_state_blocks(tq, rs.kv_state ? tkv : 0)), dim3(kSchedThreads), 0,
-                     stream, make_job(&rs), (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes),
+                     stream, make_job(&rs), max_segment_keys(kv_row_bytes),
                      MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv);
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
@@ -534,7 +534,7 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
   const int state_blocks = states ? row_state_blocks(tq, states->kv_state ? tkv : 0) : 0;
   hipLaunchKernelGGL(sched_kernel, dim3(1 + fill_blocks + state_blocks), dim3(kSchedThreads), 0, stream,
                      backward ? 1 : 0, lse_fill ? 1 : 0, tile, inner,
-                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
+                     max_segment_keys(kv_row_bytes), MaskTables{q_limit, k_from}, work, (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, n_parts,
                      (int32_t)tile_cap, hdr, item_off, item_flags, tiles, lse_fill, lse_fill_n, fill_blocks, make_job(states));
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
@@ -561,7 +561,7 @@ int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int3
   const int state_blocks = states ? row_state_blocks(tq, states->kv_state ? tkv : 0) : 0;
   hipLaunchKernelGGL(sched_bwd_kernel, dim3((unsigned)(2 + stat_blocks + state_blocks)), dim3(kSchedThreads), 0, stream,
                      job(region_kv, kBwdBN, kBwdBM, cap_kv), job(region_q, kDqBM, kDqBN, cap_q),
-                     (int32_t)(((int64_t)INT32_MAX - 4096) / kv_row_bytes), MaskTables{q_limit, k_from}, work,
+                     max_segment_keys(kv_row_bytes), MaskTables{q_limit, k_from}, work,
                      (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, lse, delta, n_stats, stats, (int)stat_blocks,
                      make_job(states));
   FCP_HIP_CHECK(hipGetLastError());

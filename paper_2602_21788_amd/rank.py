@@ -185,29 +185,3 @@ class RankAttention:
         self.backward_delta(stream)
         self.backward_steps_direct(stream)
         self.finalize_direct(stream)
-
-    # -- bookkeeping ------------------------------------------------------------------
-    def pairs(self) -> int:
-        """Visible (query, key) pairs of this rank: sum over its rows of (position + 1), or of
-        (last visible key position + 1) under a mixed mask."""
-        if self.spans is not None:
-            return int(self.q_limit.astype(np.int64).sum()) + self.tq
-        tot = 0
-        for c in self.my_chunks:
-            a, n = int(c["seq_start"]), int(c["len"])
-            tot += n * a + n * (n + 1) // 2
-        return tot
-
-    def merge_bytes(self, direct: bool = False) -> int:
-        """Algorithmic bytes of fcp_lse_merge: per row and head, each contributing slot is read
-        once (D fp32 + its LSE), every slot's LSE is read, and O (bf16) + LSE are written.  direct: those of
-        fcp_lse_merge_direct, which skips the rows that exactly one work item feeds (one state byte per row is read)."""
-        parts_per_row = np.zeros(self.tq, np.int64)
-        for w in self.work:
-            parts_per_row[int(w["q_local_off"]):int(w["q_local_off"]) + int(w["q_len"])] += 1
-        D = self.D
-        if direct:
-            merged = parts_per_row != 1
-            return int(self.hq * (parts_per_row[merged].sum() * (D * 4) + merged.sum() * (self.n_parts * 4 + D * 2 + 4))
-                       + self.tq * self.hq)
-        return int(self.hq * (parts_per_row.sum() * (D * 4) + self.tq * (self.n_parts * 4 + D * 2 + 4)))
