@@ -138,25 +138,123 @@ __device__ inline void stage_item(int32_t (&r)[7], const fcp_work_desc& a, bool 
   r[5] = a.n_seg > 1 ? a.k_seq_start[1] : 0;
   r[6] = a.n_seg > 1 ? a.k_seq_start[1] + a.k_len[1] : 0;   // empty range when absent
 }
-__device__ inline int32_t exclusive_flags(const int32_t (*rng)[7], int32_t i, int32_t n_work) {
-  if (rng[i][0] < 0) return 0;
-  int32_t flags = kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive;
-  const int32_t seq = rng[i][0], q0 = rng[i][1], q1 = rng[i][2];
-  const int32_t k0[2] = {rng[i][3], rng[i][5]}, k1[2] = {rng[i][4], rng[i][6]};
-  if (k0[0] < k1[1] && k0[1] < k1[0]) flags &= kFlagQExclusive;   // own segments overlap
-  for (int32_t j = 0; j < n_work; ++j) {
-    if (j == i || rng[j][0] < 0) continue;
-    if (q0 < rng[j][2] && rng[j][1] < q1) flags &= ~kFlagQExclusive;
-    if (rng[j][0] == seq) {
-#pragma unroll
-      for (int sa = 0; sa < 2; ++sa) {
-        if ((k0[sa] < rng[j][4] && rng[j][3] < k1[sa]) || (k0[sa] < rng[j][6] && rng[j][5] < k1[sa]))
-          flags &= ~(sa == 0 ? kFlagSeg0Exclusive : kFlagSeg1Exclusive);
+// Flags of all items at once (n_work <= kMaxExclusiveScan), by sorting instead of comparing all pairs: intervals sorted by
+// their start overlap an earlier one iff the largest end so far exceeds their start, and a later one iff the next start
+// lies before their end.  Query rows: one set over all valid items.  Key segments: one set of up to two segments per
+// item, ordered by (sequence, start); only segments of the same sequence can overlap, and an item's own two segments
+// count like anybody else's.  The sequence enters the sort key with its low 21 bits: two sequences that collide there
+// are treated as one, which can only clear a flag that could have been set (the safe side).
+// `key`: LDS work area of 2 * kMaxExclusiveScan entries; `fl`: LDS, one word per item, written here.
+__device__ inline void bitonic_sort(uint64_t* key, int32_t n_pow2) {
+  for (int32_t k = 2; k <= n_pow2; k <<= 1)
+    for (int32_t j = k >> 1; j > 0; j >>= 1) {
+      for (int32_t t = threadIdx.x; t < n_pow2 / 2; t += kSchedThreads) {
+        const int32_t i = ((t & ~(j - 1)) << 1) | (t & (j - 1)), l = i | j;
+        const uint64_t a = key[i], b = key[l];
+        if ((a > b) == ((i & k) == 0)) { key[i] = b; key[l] = a; }
       }
+      __syncthreads();
+    }
+}
+
+// Inclusive running maximum over the block's values in thread order (two per thread: v0 then v1).  `s_wmax`: 16 slots.
+__device__ inline void block_running_max(uint64_t v0, uint64_t v1, uint64_t* s_wmax, uint64_t& before0, uint64_t& before1) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint64_t inc = v0 > v1 ? v0 : v1;
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint64_t o = __shfl_up(inc, off, 64);
+    if (lane >= off && o > inc) inc = o;
+  }
+  __syncthreads();
+  if (lane == 63) s_wmax[wave] = inc;
+  __syncthreads();
+  uint64_t base = 0;
+  for (int w = 0; w < wave; ++w) base = s_wmax[w] > base ? s_wmax[w] : base;
+  uint64_t prev = __shfl_up(inc, 1, 64);        // maximum up to and including the thread before, inside the wave
+  if (lane == 0) prev = 0;
+  before0 = prev > base ? prev : base;          // maximum of everything before v0
+  before1 = before0 > v0 ? before0 : v0;        // ... before v1
+}
+
+__device__ inline void exclusive_flags_all(const int32_t (*rng)[7], int32_t n_work, uint64_t* key, uint64_t* s_wmax, int32_t* fl) {
+  const int tid = threadIdx.x;
+  constexpr uint64_t kNone = ~(uint64_t)0;
+  for (int32_t i = tid; i < n_work; i += kSchedThreads)
+    fl[i] = rng[i][0] < 0 ? 0 : (kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive);
+  // ---- query rows: key = start << 11 | item
+  int32_t np = 2;
+  while (np < n_work) np <<= 1;
+  for (int32_t i = tid; i < np; i += kSchedThreads)
+    key[i] = (i < n_work && rng[i][0] >= 0) ? ((uint64_t)(uint32_t)rng[i][1] << 11) | (uint64_t)i : kNone;
+  __syncthreads();
+  bitonic_sort(key, np);
+  {
+    // one element per thread (np <= kSchedThreads): value of the running maximum = end
+    const uint64_t k0 = tid < np ? key[tid] : kNone;
+    const bool live = k0 != kNone;
+    const int32_t item = live ? (int32_t)(k0 & 2047) : 0;
+    const uint64_t end = live ? (uint64_t)(uint32_t)rng[item][2] : 0;
+    uint64_t before, unused;
+    block_running_max(end, 0, s_wmax, before, unused);
+    if (live) {
+      const uint64_t start = k0 >> 11;
+      const uint64_t nxt = tid + 1 < np ? key[tid + 1] : kNone;
+      const bool hit = before > start || (nxt != kNone && (nxt >> 11) < end);
+      if (hit) atomicAnd(&fl[item], ~kFlagQExclusive);
     }
   }
-  return flags;
+  __syncthreads();
+  // ---- key segments: key = seq (21 bits) << 43 | start (31 bits) << 12 | slot (item * 2 + segment)
+  int32_t np2 = 2;
+  while (np2 < 2 * n_work) np2 <<= 1;
+  for (int32_t sl = tid; sl < np2; sl += kSchedThreads) {
+    const int32_t i = sl >> 1, sg = sl & 1;
+    uint64_t k = kNone;
+    if (i < n_work && rng[i][0] >= 0) {
+      const int32_t a = rng[i][3 + 2 * sg], b = rng[i][4 + 2 * sg];
+      if (b > a) k = ((uint64_t)(rng[i][0] & 0x1FFFFF) << 43) | ((uint64_t)(uint32_t)a << 12) | (uint64_t)sl;
+    }
+    key[sl] = k;
+  }
+  __syncthreads();
+  bitonic_sort(key, np2);
+  {
+    // two consecutive elements per thread; value of the running maximum = seq << 32 | end
+    auto unpack = [&](uint64_t k, uint64_t& val, uint64_t& seqm, uint64_t& start, int32_t& slot) {
+      slot = (int32_t)(k & 4095);
+      start = (k >> 12) & 0x7FFFFFFFu;
+      seqm = k >> 43;
+      val = (seqm << 32) | (uint64_t)(uint32_t)rng[slot >> 1][4 + 2 * (slot & 1)];
+    };
+    const int32_t p0 = 2 * tid, p1 = 2 * tid + 1;
+    const uint64_t k0 = p0 < np2 ? key[p0] : kNone, k1 = p1 < np2 ? key[p1] : kNone;
+    uint64_t v0 = 0, v1 = 0, q0 = 0, q1 = 0, st0 = 0, st1 = 0;
+    int32_t sl0 = 0, sl1 = 0;
+    if (k0 != kNone) unpack(k0, v0, q0, st0, sl0);
+    if (k1 != kNone) unpack(k1, v1, q1, st1, sl1);
+    uint64_t b0, b1;
+    block_running_max(v0, v1, s_wmax, b0, b1);
+    const uint64_t k2 = p1 + 1 < np2 ? key[p1 + 1] : kNone;
+    auto test = [&](uint64_t k, uint64_t val, uint64_t seqm, uint64_t start, int32_t slot, uint64_t before, uint64_t nxt) {
+      if (k == kNone) return;
+      bool hit = (before >> 32) == seqm && (before & 0xFFFFFFFFu) > start;            // an earlier segment of the sequence ends after this start
+      if (nxt != kNone && (nxt >> 43) == seqm && ((nxt >> 12) & 0x7FFFFFFFu) < (val & 0xFFFFFFFFu)) hit = true;   // the next one starts before this end
+      if (hit) atomicAnd(&fl[slot >> 1], ~((slot & 1) ? kFlagSeg1Exclusive : kFlagSeg0Exclusive));
+    };
+    test(k0, v0, q0, st0, sl0, b0, k1);
+    test(k1, v1, q1, st1, sl1, b1, k2);
+  }
+  __syncthreads();
 }
+
+// LDS shared between the flags' sort (first) and the list builder's histogram and offsets (afterwards).
+struct SortArea {
+  union {
+    uint64_t key[2 * kMaxExclusiveScan];
+    struct { int32_t hist[kBuckets]; int32_t off[kMaxExclusiveScan + 1]; } later;
+  };
+  uint64_t wmax[kSchedThreads / 64];
+};
 
 // One tile list, built by one block.
 __device__ void build_list(
@@ -164,13 +262,27 @@ __device__ void build_list(
     const fcp_work_desc* __restrict__ work, int32_t n_work,
     const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv, int32_t n_parts,
     int32_t tile_cap, SchedHeader* hdr, int32_t* item_off, int32_t* item_flags, Tile* tiles,
-    int32_t (*s_rng)[7]) {               // LDS, kMaxExclusiveScan rows: seq (-1 = invalid), q range, two key ranges
+    int32_t (*s_rng)[7],                 // LDS, kMaxExclusiveScan rows: seq (-1 = invalid), q range, two key ranges
+    SortArea* area, int32_t* s_fl) {     // LDS: sort keys (later the histogram and the offsets), one flag word per item
   __shared__ int32_t s_wave[kSchedThreads / 64];
-  __shared__ int32_t s_hist[kBuckets];
   __shared__ int32_t s_max, s_rej, s_carry;
-  __shared__ int32_t s_off[kMaxExclusiveScan + 1];    // copy of item_off for short work lists: the tile decode below
+  int32_t* const s_hist = area->later.hist;
+  int32_t* const s_off = area->later.off;          // copy of item_off for short work lists: the tile decode below
   const bool off_in_lds = n_work <= kMaxExclusiveScan;   // searches it, and a search in global memory is a chain of misses
   const int tid = threadIdx.x;
+  // The exclusivity flags first: their sort keys share LDS with the histogram and the offsets.
+  if (n_work <= kMaxExclusiveScan) {
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) {
+      const fcp_work_desc a = work[i];
+      stage_item(s_rng[i], a, item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys));
+    }
+    __syncthreads();
+    exclusive_flags_all(s_rng, n_work, area->key, area->wmax, s_fl);
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = s_fl[i];
+  } else {
+    for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = 0;
+  }
+  __syncthreads();
   if (tid == 0) { s_max = 0; s_rej = 0; s_carry = 0; }
   for (int b = tid; b < kBuckets; b += kSchedThreads) s_hist[b] = 0;
   __syncthreads();
@@ -197,16 +309,6 @@ __device__ void build_list(
     if (tid == 0) s_carry = carry + total;
     __syncthreads();
   }
-  if (n_work <= kMaxExclusiveScan) {
-    for (int32_t i = tid; i < n_work; i += kSchedThreads) {
-      const fcp_work_desc a = work[i];
-      stage_item(s_rng[i], a, item_valid(a, cu, n_seqs, tq, tkv, n_parts, check_step != 0, max_seg_keys));
-    }
-    __syncthreads();
-    for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = exclusive_flags(s_rng, i, n_work);
-  } else {
-    for (int32_t i = tid; i < n_work; i += kSchedThreads) item_flags[i] = 0;
-  }
   const int32_t total_tiles = s_carry;
   const int32_t n_tiles = min(total_tiles, tile_cap);
   if (tid == 0) {
@@ -227,7 +329,7 @@ __device__ void build_list(
     const fcp_work_desc w = work[lo];
     const int32_t local = t - (off_in_lds ? s_off[lo] : item_off[lo]);
     const int32_t row0_kv = cu[w.seq];
-    const int32_t fl = item_flags[lo];
+    const int32_t fl = off_in_lds ? s_fl[lo] : 0;
     for (int i = 0; i < 16; ++i) out.w[i] = 0;
     if (!backward) {
       QTile* q = reinterpret_cast<QTile*>(&out);
@@ -321,7 +423,7 @@ struct RowStateJob {
 __device__ void row_states(
     int first, int count, const RowStateJob& job, int32_t max_seg_keys, const MaskTables& m,
     const fcp_work_desc* __restrict__ work, int32_t n_work, const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq,
-    int32_t tkv, int32_t (*s_rng)[7], int32_t (*s_vis)[2], uint8_t* s_fl) {
+    int32_t tkv, int32_t (*s_rng)[7], int32_t (*s_vis)[2], int32_t* s_fl, SortArea* area) {
   uint8_t* __restrict__ q_state = job.q_state;
   uint8_t* __restrict__ kv_state = job.kv_state;
   float* __restrict__ dq_acc = job.dq_acc;
@@ -338,8 +440,7 @@ __device__ void row_states(
     s_vis[i][1] = ok && a.n_seg > 1 ? visible_len(m, a, 1, a.q_len - 1) : 0;
   }
   __syncthreads();
-  for (int32_t i = tid; i < n_work; i += kSchedThreads) s_fl[i] = (uint8_t)exclusive_flags(s_rng, i, n_work);
-  __syncthreads();
+  exclusive_flags_all(s_rng, n_work, area->key, area->wmax, s_fl);
 
   const int64_t n_rows = (int64_t)tq + n_kv_rows;     // (the forward classifies its query rows only)
   const int64_t wave0 = (int64_t)(blockIdx.x - first) * (kSchedThreads / 64) + (tid >> 6);
@@ -396,8 +497,9 @@ __global__ __launch_bounds__(kSchedThreads) void row_state_kernel(
     int32_t n_work, const int32_t* __restrict__ cu, int32_t n_seqs, int32_t tq, int32_t tkv) {
   __shared__ int32_t s_rng[kMaxExclusiveScan][7];
   __shared__ int32_t s_vis[kMaxExclusiveScan][2];   // keys of each segment that the item's last row sees
-  __shared__ uint8_t s_fl[kMaxExclusiveScan];
-  row_states(0, gridDim.x, job, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, s_rng, s_vis, s_fl);
+  __shared__ int32_t s_fl[kMaxExclusiveScan];
+  __shared__ SortArea s_area;
+  row_states(0, gridDim.x, job, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, s_rng, s_vis, s_fl, &s_area);
 }
 
 // Forward: block 0 builds the query-tile list, the next `fill_blocks` blocks pre-fill the partial LSE with -inf,
@@ -410,18 +512,19 @@ __global__ __launch_bounds__(kSchedThreads) void sched_kernel(
     float* lse_fill, int64_t lse_fill_n, int fill_blocks, const RowStateJob states) {
   __shared__ int32_t s_rng[kMaxExclusiveScan][7];
   __shared__ int32_t s_vis[kMaxExclusiveScan][2];
-  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+  __shared__ int32_t s_fl[kMaxExclusiveScan];
+  __shared__ SortArea s_area;
   const int b = blockIdx.x;
   if (b == 0) {
     build_list(backward, check_step, tile, inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, n_parts, tile_cap,
-               hdr, item_off, item_flags, tiles, s_rng);
+               hdr, item_off, item_flags, tiles, s_rng, &s_area, s_fl);
   } else if (b <= fill_blocks) {
     const int64_t stride = (int64_t)fill_blocks * kSchedThreads;
     for (int64_t i = (int64_t)(b - 1) * kSchedThreads + threadIdx.x; i < lse_fill_n; i += stride)
       lse_fill[i] = -INFINITY;
   } else {
     row_states(1 + fill_blocks, gridDim.x - 1 - fill_blocks, states, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv,
-               s_rng, s_vis, s_fl);
+               s_rng, s_vis, s_fl, &s_area);
   }
 }
 
@@ -444,12 +547,13 @@ __global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
     int stat_blocks, const RowStateJob states) {
   __shared__ int32_t s_rng[kMaxExclusiveScan][7];
   __shared__ int32_t s_vis[kMaxExclusiveScan][2];
-  __shared__ uint8_t s_fl[kMaxExclusiveScan];
+  __shared__ int32_t s_fl[kMaxExclusiveScan];
+  __shared__ SortArea s_area;
   const int b = blockIdx.x;
   if (b < 2) {
     const ListJob& j = b == 0 ? kv : qt;
     build_list(b == 0 ? 1 : 0, 0, j.tile, j.inner, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv, 1,
-               j.tile_cap, j.hdr, j.item_off, j.item_flags, j.tiles, s_rng);
+               j.tile_cap, j.hdr, j.item_off, j.item_flags, j.tiles, s_rng, &s_area, s_fl);
   } else if (b < 2 + stat_blocks) {
     const int64_t stride = (int64_t)stat_blocks * kSchedThreads;
     for (int64_t i = (int64_t)(b - 2) * kSchedThreads + threadIdx.x; i < n_stats; i += stride) {
@@ -459,7 +563,7 @@ __global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
     }
   } else {   // direct mode: the row states, and the accumulator rows that are accumulated into cleared
     row_states(2 + stat_blocks, gridDim.x - 2 - stat_blocks, states, max_seg_keys, m, work, n_work, cu, n_seqs, tq, tkv,
-               s_rng, s_vis, s_fl);
+               s_rng, s_vis, s_fl, &s_area);
   }
 }
 
