@@ -9,50 +9,56 @@
 // retire at about one element per L2 channel per clock on this chip (~270 G/s), far too few to accumulate dQ
 // per key tile.
 //
-// dq_kernel: persistent 768-thread blocks (12 wave64, one block per CU, three waves per SIMD) pull
-// (query tile, query head) units from per-XCD counters.  A unit = 128 query rows of one work item for one query
-// head, looping over the 32-key blocks ("steps") of the two key segments that its rows see.  K and V blocks
-// stream through LDS in five stages filled by LDS-direct buffer loads; the K tile is chunk-permuted so that both
-// row reads and transpose reads run at the full LDS rate.  The three waves of a SIMD split a step by role (the
-// reasons are those given for the dK/dV kernel):
-//   P wave:  S^T = K Q^T [key x query] for its 32 query rows (Q fragments in registers, one query per lane, so
-//            LSE and the causal bound are per-lane constants), P^T = exp2(c S^T - LSE log2 e) with the mask,
-//            left in LDS in bf16 B-operand form;
-//   dS wave: dP^T - delta = V dO^T with the accumulator started at -delta (dO fragments in registers); one step
-//            later dS^T = P^T o (dP^T - delta) -> LDS bf16;
-//   dQ wave: dQ^T += K^T dS^T, two steps behind, for 64 channels x 64 query rows (the rows of two P waves), K^T
-//            by transpose reads, each feeding two matrix instructions.
-// One block barrier per step.  The result is added to the caller's fp32 accumulator once per unit: with plain
+// dq_kernel: persistent 512-thread blocks (8 wave64, one block per CU, two waves per SIMD, up to 256 registers each) pull
+// units from per-XCD counters.  A unit = 128 query rows of one work item for TWO query heads of one KV head (waves
+// 0..3 the first head, waves 4..7 the second), or, when the heads per KV head are odd, 256 rows for one head; either
+// way the eight waves share every K / V block, looping over the 32-key blocks ("steps") of the two key segments that
+// the rows see.  K and V blocks stream through LDS in four stages filled by LDS-direct buffer loads; the tiles are
+// chunk-permuted so that both row reads and transpose reads run at the full LDS rate.  The waves are INDEPENDENT: each
+// owns 32 query rows (Q and dO fragments in registers, one query per lane, so LSE, delta and the causal bound are
+// per-lane constants) and does everything for them, so nothing is handed from wave to wave and the only block-wide
+// meeting is the one barrier per step that recycles the LDS stages.  Per step and wave:
+//   A  S^T = K Q^T and dP^T = V dO^T [key x query] for the step's 32 keys (row reads of K and V),
+//   V  P^T = exp2(c S^T - LSE log2 e) with the mask, dS^T = P^T o (dP^T - delta), bf16, in registers in the A-operand form of
+//   Q  dQ += dS K [query x channel] (K^T by transpose reads).
+// A single wave issues about one instruction every six cycles whatever its kind, so the vector work of one wave has to
+// meet the matrix work of ANOTHER wave of its SIMD: waves w and w + 4 share a SIMD, and the second group runs its steps
+// shifted - between two barriers waves 0..3 do A V Q of step `it`, waves 4..7 do V Q of step it - 1 and then A of step
+// `it` - so that one of the two is in its contraction while the other exponentiates.
+// (The role-split predecessor of this kernel - P, dS and dQ waves exchanging bf16 tiles through LDS, 12 waves - spent
+// its steps in the hand-over chain barrier -> LDS -> matrix -> exponentials -> LDS -> barrier.)
+// The result is added to the caller's fp32 accumulator once per unit: with plain
 // load-add-store when the scheduler found that no other item of the launch touches the same rows (always the
 // case for degree-1 sequences), otherwise with fp32 atomics.
 #include "fcp_bwd.h"
+
+#include <type_traits>
 
 namespace fcp {
 namespace {
 
 template <int D>
 struct DqCfg {
-  static constexpr int BM = kDqBM;                 // 128 query rows per unit (32 per P / dS wave)
   static constexpr int BK = kDqBN;                 // keys per step
-  static constexpr int NWAVE = 12;
+  static constexpr int NWAVE = 8;
   using DT = DualTile<D>;
   static constexpr int TILE = DT::bytes(BK);       // one K or V block
   static constexpr int STAGE = 2 * TILE;           // K, V
   static constexpr int FILL_AHEAD = 2;             // steps between a block's fill and its first use
-  static constexpr int NSTAGE = 3 + FILL_AHEAD;    // two steps behind, the step itself, FILL_AHEAD steps ahead
-  static constexpr int PB = 32 * 32 * 2;           // P^T or dS^T of one query group in bf16, B-operand form
-  static constexpr int XGROUP = 2 * PB + 2 * PB;   // each double-buffered by step parity
-  static constexpr int XOFF = NSTAGE * STAGE;
-  static constexpr int LDS_BYTES = XOFF + 4 * XGROUP;
-  static constexpr int NS = D / 16;                // MFMAs of one 32 x 32 block of S^T or dP^T
-  static constexpr int NVA = D / 64;               // 32-channel blocks of dQ^T per dQ wave (half of the channels)
+  static constexpr int NSTAGE = 2 + FILL_AHEAD;    // one step behind (the second wave group), the step itself, FILL_AHEAD ahead
+  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  static constexpr int NS = D / 16;                // k-steps of one 32 x 32 block of S^T or dP^T
+  static constexpr int NCB = D / 32;               // 32-channel blocks of dQ
   static constexpr int TINST = 2 * BK / DT::RPI;   // tile fill instructions per step (K then V)
-  static constexpr int kAhead = 4;
-  static_assert(TINST <= 2 * NWAVE, "at most two tile instructions per wave");
+  static constexpr int IPW = TINST / NWAVE;        // ... per wave: waves 0..3 fill K, waves 4..7 fill V
+  static constexpr int NQ = 2 * NCB;               // matrix instructions of a step's accumulation
+  static constexpr int kAhead = 4;                 // row fragments requested this many matrix instructions ahead
+  static_assert(IPW * NWAVE == TINST && IPW >= 1, "fill split");
+  static_assert(BK == 32, "one 32 x 32 score block per wave and step");
 };
 
 template <int D>
-__global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
+__global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int head_pair) {
   using C = DqCfg<D>;
   using DT = typename C::DT;
   extern __shared__ __attribute__((aligned(256))) unsigned char smem[];
@@ -61,41 +67,54 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int role = wave >> 2;                     // 0: P, 1: dS, 2: dQ
-  const int pw = wave & 3;                        // query group (and SIMD): rows 32 pw .. 32 pw + 31
+  const int grp = wave >> 2;                      // 0: waves 0..3, 1: waves 4..7 (the shifted group)
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = p.hq / p.hkv;
   const uint32_t lds0 = lds_offset(smem);
-  const bool per_xcd = (p.hq % kNumXcd) == 0;
+  // unit numbering: when the heads split evenly each XCD owns a contiguous eighth of them (so the K/V of a KV head stay
+  // in one L2); a unit covers one head or, in head-pair mode, two consecutive heads
+  const int hpu = head_pair ? 2 : 1;
+  const bool per_xcd = (p.hq % (kNumXcd * hpu)) == 0;
   const int xcd = per_xcd ? (int)(blockIdx.x % kNumXcd) : 0;
   const int heads_here = per_xcd ? p.hq / kNumXcd : p.hq;
+  const int units_per_tile = heads_here / hpu;
   UnitQueue uq;
-  uq.init(p.hdr, p.tiles, xcd, heads_here, &s_next_unit, s_rec);
+  uq.init(p.hdr, p.tiles, xcd, units_per_tile, &s_next_unit, s_rec);
 
-  // ---- per-wave fill duty: tile instructions `wave` and `wave + 12` where they exist (the first half of the
-  // instructions fills K, the second V; instruction j covers block rows RPI (j % (TINST/2)) ..)
+  // ---- per-wave fill duty: IPW tile instructions of K (waves 0..3) or of V (waves 4..7); instruction j of a block
+  // covers its rows RPI j ..  (the chunk permutation depends on the rows, so every instruction has its own offsets)
   const int kv_row_bytes = p.hkv * D * 2;
-  int tfill[2], fill_dst[2];
-  bool fill_on[2], fill_is_v[2];
+  const bool fill_is_v = wave >= 4;
+  int tfill[C::IPW], fill_dst[C::IPW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int j = wave + C::NWAVE * i;
-    fill_on[i] = j < C::TINST;
-    fill_is_v[i] = j >= C::TINST / 2;
-    const int row0 = DT::RPI * (j % (C::TINST / 2));
+  for (int i = 0; i < C::IPW; ++i) {
+    const int row0 = DT::RPI * (C::IPW * (wave & 3) + i);
     const int row = row0 + lane / DT::CPR;
     tfill[i] = row * kv_row_bytes + (((lane % DT::CPR) ^ DT::key(row)) << 4);
-    fill_dst[i] = (fill_is_v[i] ? C::TILE : 0) + DT::row_base(row0);
+    fill_dst[i] = (fill_is_v ? C::TILE : 0) + DT::row_base(row0);
+  }
+  // row fragments (A operands of S^T = K Q^T, dP^T = V dO^T): lane reads block row (key) l32, chunk 2 ks + g2
+  int rowaddr[C::NS];
+#pragma unroll
+  for (int ks = 0; ks < C::NS; ++ks) rowaddr[ks] = tile_off<DT>(l32, 2 * ks + g2);
+  // transposed fragments of the K block (B operand K [key x channel], one channel per lane; k-slots = keys 16 t + {4 g2 + [0,4),
+  // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
+  // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
+  int traddr[2][C::NCB];
+  {
+    const int row0 = 4 * g2 + ((lane & 15) >> 2);
+    const int chunk0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int db = 0; db < C::NCB; ++db) traddr[h][db] = tile_off<DT>(row0 + 8 * h, 4 * db + chunk0) + 8 * (lane & 1);
   }
 
-  unsigned char* const xg = smem + C::XOFF + pw * C::XGROUP + lane * 16;
-  unsigned char* const x_pb = xg;                       // + parity * PB + j * 1024, j < 2
-  unsigned char* const x_ds = xg + 2 * C::PB;
   for (;;) {
     const int unit = uq.current(&s_next_unit);
     if (unit >= uq.n_units) break;
     const QTile t = read_record<QTile, 12>(s_rec);
-    const int head = xcd * heads_here + unit % heads_here;
+    const int head = xcd * heads_here + (unit % units_per_tile) * hpu + (head_pair ? grp : 0);
     const int kvh = head / G;
     uq.prefetch();
 
@@ -114,11 +133,11 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
     // resources' range), which the vmcnt waits rely on.  Keys past the segment's visible part lie outside the
     // range and arrive as zeros.
     int f_seg = nt0 > 0 ? 0 : 1, f_left = nt0 > 0 ? nt0 : nt1, f_soff = 0;
-    auto f_resource = [&](int i, int seg, bool live) {
-      const uint16_t* base = (fill_is_v[i] ? p.v : p.k) + ((seg ? kvrow1 : kvrow0) * p.hkv + kvh) * D;
+    auto f_resource = [&](int seg, bool live) {
+      const uint16_t* base = (fill_is_v ? p.v : p.k) + ((seg ? kvrow1 : kvrow0) * p.hkv + kvh) * D;
       return buffer_rsrc(base, live ? ((seg ? vis1 : vis0) - 1) * kv_row_bytes + D * 2 : 0);
     };
-    i32x4 f_r0 = f_resource(0, f_seg, n_iter > 0), f_r1 = f_resource(1, f_seg, n_iter > 0);
+    i32x4 f_r = f_resource(f_seg, n_iter > 0);
     uint32_t f_dst = lds0;
     auto fill_next = [&]() {
       if (f_left == 0) {          // segment 1 (or past the end: empty resources)
@@ -126,286 +145,206 @@ __global__ __launch_bounds__(768, 1) void dq_kernel(const BwdParams p) {
         f_seg = 1;
         f_left = live ? nt1 : (1 << 30);
         f_soff = 0;
-        f_r0 = f_resource(0, 1, live);
-        f_r1 = f_resource(1, 1, live);
+        f_r = f_resource(1, live);
       }
-      if (fill_on[0]) lds_fill_b128(f_r0, f_dst + fill_dst[0], tfill[0], f_soff);
-      if (fill_on[1]) lds_fill_b128(f_r1, f_dst + fill_dst[1], tfill[1], f_soff);
+#pragma unroll
+      for (int i = 0; i < C::IPW; ++i) lds_fill_b128(f_r, f_dst + fill_dst[i], tfill[i], f_soff);
       --f_left;
       f_soff += C::BK * kv_row_bytes;
       f_dst += C::STAGE;
       if (f_dst == lds0 + C::NSTAGE * C::STAGE) f_dst = lds0;
     };
-    auto wait_fills = [&]() {     // all but the newest batch of this wave's fills have landed
-      // One wait for every wave (no branch on the wave's number of fills per step, 0..2): with at most
-      // FILL_AHEAD - 1 loads in flight everything older than the newest FILL_AHEAD - 1 batches has landed; a wave
-      // with two loads per step waits for a little more than it must.
-      __builtin_amdgcn_s_waitcnt(0x0F70 | (C::FILL_AHEAD - 1));
-    };
+    // all but the newest batch of this wave's fills have landed
+    auto wait_fills = [&]() { __builtin_amdgcn_s_waitcnt(0x0F70 | C::IPW); };
 
     // Geometry.  Step s < nt0 is key block s of segment 0, step s >= nt0 block s - nt0 of segment 1; inside a segment
-    // the key positions grow with the step.  A query group takes part in the leading blocks of a segment (those whose
-    // first key the group's last row still sees) and needs no mask in the leading blocks that all its rows see in
+    // the key positions grow with the step.  The wave's rows take part in the leading blocks of a segment (those whose
+    // first key the group's last row still sees) and need no mask in the leading blocks that all its rows see in
     // full; both counts are found once per unit, so that a step costs a few compares instead of its positions.
-    struct Span { int a0, b1, u0, u1; };     // active: s < a0 or nt0 <= s < b1; unmasked: s < u0 or nt0 <= s < u1
-    auto group_span = [&](int grp) {
-      Span sp = {0, 0, 0, 0};
-      if (32 * grp >= rows_here) return sp;
+    const int wave_r0 = 32 * (head_pair ? (wave & 3) : wave);
+    const int my_row = wave_r0 + l32;
+    const int row_ld = min(my_row, rows_here - 1);
+    int a0 = 0, b1 = 0, u0 = 0, u1 = 0;     // active: s < a0 or nt0 <= s < b1; unmasked: s < u0 or nt0 <= s < u1
+    if (wave_r0 < rows_here) {
       // last key position seen by the group's first and by its last row (the limits grow with the row)
-      int first = t.q_pos0 + 32 * grp, last = t.q_pos0 + min(32 * grp + 31, rows_here - 1);
+      int first = t.q_pos0 + wave_r0, last = t.q_pos0 + min(wave_r0 + 31, rows_here - 1);
       if (p.q_limit) {
-        first = p.q_limit[t.q_row0 + 32 * grp];
-        last = p.q_limit[t.q_row0 + min(32 * grp + 31, rows_here - 1)];
+        first = p.q_limit[t.q_row0 + wave_r0];
+        last = p.q_limit[t.q_row0 + min(wave_r0 + 31, rows_here - 1)];
       }
       auto count = [&](int kpos, int vis, int nt, int& act, int& unm) {
         act = last >= kpos ? min(nt, ((last - kpos) >> 5) + 1) : 0;                 // blocks with kpos + 32 kt <= last
         const int full = first - kpos - 31 >= 0 ? ((first - kpos - 31) >> 5) + 1 : 0;   // ... with kpos + 32 kt + 31 <= first
         unm = min(full, vis / C::BK);                                              // and all 32 keys valid
       };
-      int a1, u1;
-      count(kpos0, vis0, nt0, sp.a0, sp.u0);
-      count(kpos1, vis1, nt1, a1, u1);
-      sp.b1 = nt0 + a1;
-      sp.u1 = nt0 + u1;
-      return sp;
-    };
-    auto in_span = [&](int s, int lo_end, int hi_end) { return s < lo_end || (s >= nt0 && s < hi_end); };
-    const unsigned char* stage = smem;
-    auto next_stage = [&](const unsigned char* s) { s += C::STAGE; return s == smem + C::NSTAGE * C::STAGE ? smem : s; };
+      int a1, v1;
+      count(kpos0, vis0, nt0, a0, u0);
+      count(kpos1, vis1, nt1, a1, v1);
+      b1 = nt0 + a1;
+      u1 = nt0 + v1;
+    }
+    auto in_span = [&](int s, int lo_end, int hi_end) { return s >= 0 && (s < lo_end || (s >= nt0 && s < hi_end)); };
 
-    // Iteration `it` of the n_iter + 2 of a unit: the P and dS waves contract step it, the dS wave's vector phase
-    // works on step it - 1, the dQ wave on step it - 2.  At the top every wave has waited for all its fills but the
-    // newest batch (step it + 1) and met the others, so the blocks of steps it - 2 .. it are in LDS, P^T of step
-    // it - 1 and dS^T of step it - 2 are in their buffers, and the stage of step it - 3 is free for step it + 2.
-    if (role < 2) {
-      const Span sp = group_span(pw);
-      const int my_row = 32 * pw + l32;
-      const int row_ld = min(my_row, rows_here - 1);
-      // The first fills go out before the wave's own loads so that their latencies overlap.
+    // The first fills go out before the wave's own loads so that their latencies overlap.
 #pragma unroll
-      for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
-      // own-row fragments, B operand (lane = query column), channels 16 ks + 8 g2 + [0,8): Q (P wave) or dO (dS wave)
-      bf16x8 qf[C::NS];
-      {
-        const uint16_t* src = role == 0 ? p.q : p.d_o;
-        const int64_t off = ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
+    for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
+    // own-row fragments, B operands (lane = query column), channels 16 ks + 8 g2 + [0,8): Q and dO
+    bf16x8 qf[C::NS], dof[C::NS];
+    {
+      const int64_t off = ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
 #pragma unroll
-        for (int ks = 0; ks < C::NS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + off + 16 * ks);
+      for (int ks = 0; ks < C::NS; ++ks) {
+        qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
+        dof[ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
       }
-      // -LSE log2 e (P wave) or -delta (dS wave) of the lane's row
-      const float stat = p.stats[(int64_t)role * p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
-      int q_lim = t.q_pos0 + my_row;                 // last key position the lane's row sees
-      if (p.q_limit) q_lim = p.q_limit[t.q_row0 + row_ld];
-      // These loads must have arrived before the step loop: the compiler, which does not see the fills, would
-      // otherwise wait for them inside the loop with vmcnt(0), and that wait also covers every fill in flight.
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      int rowaddr[C::NS];          // row fragments (A operand): lane reads block row (key) l32, chunk 2 ks + g2
+    }
+    // -LSE log2 e and -delta of the lane's row
+    const float stat_p = p.stats[(int64_t)head * p.tq + t.q_row0 + row_ld];
+    const float stat_d = p.stats[(int64_t)p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
+    int q_lim = t.q_pos0 + my_row;                 // last key position the lane's row sees
+    if (p.q_limit) q_lim = p.q_limit[t.q_row0 + row_ld];
+    // dQ [32-channel block] as [query x channel]: the channel is on the lane, register i is row 8 (i/4) + 4 g2 + i%4 of
+    // the wave's 32, so that a wave-wide access covers whole 128-byte lines of two rows.
+    // When no other item of the launch touches the tile's rows the accumulators START at the caller's values
+    // (divided by the scale that the epilogue applies) and the epilogue only stores.
+    // The rows are reached through a buffer resource that ends with the tile's last row (reads past it give zero,
+    // writes are dropped): per-lane offset = the lane's part (row 4 g2 of a group of eight, channel l32), scalar
+    // offset = the rest.
+    f32x16 acc[C::NCB];
+    const int row_bytes = p.hq * D * 4;
+    const int n_wave_rows = rows_here - wave_r0;                 // rows of the tile from this wave's first on
+    const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(p.dq + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
+        n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 4 : 0, 0x00020000);
+    const int acc_voff = 4 * g2 * row_bytes + 4 * l32;
+    auto acc_soff = [&](int db, int i) { return (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db; };
+    // Direct mode: the unit owns its rows, so nothing is read and the epilogue writes the final bf16 rows.
+    const bool direct = exclusive && p.dq_out != nullptr;
 #pragma unroll
-      for (int ks = 0; ks < C::NS; ++ks) rowaddr[ks] = tile_off<DT>(l32, 2 * ks + g2);
-      // S^T or dP^T - delta [32 keys x 32 own rows]; register i is key 8 (i/4) + 4 g2 + i%4 of the block
-      auto contract = [&](f32x16& sacc, const unsigned char* rtile) {
-        bf16x8 fr[C::NS];
-        auto request = [&](int x) { if (x < C::NS) fr[x] = *reinterpret_cast<const bf16x8*>(rtile + rowaddr[x]); };
-#pragma unroll
-        for (int x = 0; x < C::kAhead; ++x) request(x);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int x = 0; x < C::NS; ++x) {
-          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[x], qf[x], sacc, 0, 0, 0);
-          request(x + C::kAhead);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      };
-      if (role == 0) {
-        for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
-          wait_fills();
-          __syncthreads();
-          fill_next();
-          if (!in_span(it, sp.a0, sp.b1)) continue;
-          f32x16 sacc = zero16();
-          contract(sacc, stage);
-          // P^T = exp2(c S^T - LSE log2 e); masked where the key is past the block's valid keys or after the row.
-          // Rows past the tile's last row repeat the last row and are never stored.
-          const bool need_mask = !in_span(it, sp.u0, sp.u1);
-          bf16x8 pb[2];
-          if (need_mask) {
-            const bool seg1 = it >= nt0;
-            const int kt = it - (seg1 ? nt0 : 0);
-            const int k_pos0 = (seg1 ? kpos1 : kpos0) + kt * C::BK;
-            const int n_valid = min(C::BK, (seg1 ? vis1 : vis0) - kt * C::BK);
-            int hi = min(n_valid, q_lim - k_pos0 + 1) - 4 * g2;     // keys (minus 4 g2) below this bound are seen
-            asm volatile("; masked variant" : "+v"(hi));
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const float e = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, stat));
-              pb[i / 8][i % 8] = (__bf16)((8 * (i / 4) + (i % 4) < hi) ? e : 0.f);
-            }
-          } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) pb[i / 8][i % 8] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, stat));
-          }
-#pragma unroll
-          for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_pb + (it & 1) * C::PB + j * 1024) = pb[j];
-        }
-      } else {
-        bool prev_active = false;
-        f32x16 dpacc = zero16();   // dP^T - delta of step it - 1 at the top of iteration it
-        for (int it = 0; it < n_iter + 2; ++it, stage = next_stage(stage)) {
-          wait_fills();
-          __syncthreads();
-          fill_next();
-          const bool active = in_span(it, sp.a0, sp.b1);
-          if (prev_active) {
-            // dS^T = P^T o (dP^T - delta) of step it - 1, with P as the matrix pipe would see it (bf16)
-            bf16x8 pin[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) pin[j] = *reinterpret_cast<const bf16x8*>(x_pb + ((it - 1) & 1) * C::PB + j * 1024);
-            bf16x8 dsb[2];
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dsb[i / 8][i % 8] = (__bf16)((float)pin[i / 8][i % 8] * dpacc[i]);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) *reinterpret_cast<bf16x8*>(x_ds + ((it - 1) & 1) * C::PB + j * 1024) = dsb[j];
-          }
-          if (active) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) dpacc[i] = stat;     // the accumulator starts at -delta of the lane's row
-            contract(dpacc, stage + C::TILE);
-          }
-          prev_active = active;
-        }
-      }
-    } else {
-      // dQ waves: 64 query rows (the groups 2 qp, 2 qp + 1 of two P / dS waves) x 64 channels (half ch).
-      const int qp = pw >> 1, ch = pw & 1;
-      const Span sp0 = group_span(2 * qp), sp1 = group_span(2 * qp + 1);
-      // transposed fragments of the K block (B operand K [key x channel], one channel per lane; k-slots = keys 16 t + {4 g2 + [0,4),
-      // 8 + 4 g2 + [0,4)}): inside a 16-lane block lane i supplies the address of block row (i / 4), channels
-      // 4 (i % 4) + [0,4); block b covers channels 16 (b % 2) + [0,16) for row group b / 2
-      int traddr[2][C::NVA];
-      {
-        const int row0 = 4 * g2 + ((lane & 15) >> 2);
-        const int chunk0 = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-          for (int db = 0; db < C::NVA; ++db)
-            traddr[h][db] = tile_off<DT>(row0 + 8 * h, 4 * (C::NVA * ch + db) + chunk0) + 8 * (lane & 1);
-      }
-#pragma unroll
-      for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
-      // dQ [32-channel block][query group of the pair] as [query x channel]: the channel is on the lane, register i is
-      // row 8 (i/4) + 4 g2 + i%4 of the group, so that a wave-wide access covers whole 128-byte lines of two rows.
-      // When no other item of the launch touches the tile's rows the accumulators START at the caller's values
-      // (divided by the scale that the epilogue applies) and the epilogue only stores: the loads overlap the other
-      // waves' prologue loads instead of standing, as a read-modify-write at the end, between two units.
-      // The rows are reached through a buffer resource that ends with the tile's last row (reads past it give zero,
-      // writes are dropped): per-lane offset = the lane's part (row 4 g2 of a group of eight, channel l32), scalar
-      // offset = the rest.
-      f32x16 acc[C::NVA][2];
-      const int row_bytes = p.hq * D * 4;
-      const int n_pair_rows = rows_here - 64 * qp;                 // rows of the tile in this wave's 64-row half
-      const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
-          (void*)(p.dq + ((int64_t)(t.q_row0 + 64 * qp) * p.hq + head) * D + 32 * C::NVA * ch), (short)0,
-          n_pair_rows > 0 ? (n_pair_rows - 1) * row_bytes + 32 * C::NVA * 4 : 0, 0x00020000);
-      const int acc_voff = 4 * g2 * row_bytes + 4 * l32;
-      auto acc_soff = [&](int kb, int db, int i) { return (32 * kb + 8 * (i / 4) + (i % 4)) * row_bytes + 128 * db; };
-      // Direct mode: the unit owns its rows, so nothing is read and the epilogue writes the final bf16 rows.
-      const bool direct = exclusive && p.dq_out != nullptr;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int db = 0; db < C::NVA; ++db) {
-          acc[db][kb] = zero16();
-          if (exclusive && !direct) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-              acc[db][kb][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(racc, acc_voff, acc_soff(kb, db, i), 0));
-          }
-        }
-      // (explicit wait: see the note at the P / dS waves' loads)
-      __builtin_amdgcn_s_waitcnt(0x0F70);
+    for (int db = 0; db < C::NCB; ++db) {
+      acc[db] = zero16();
       if (exclusive && !direct) {
-        const float inv_scale = 1.f / p.scale;
 #pragma unroll
-        for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[db][kb][i] *= inv_scale;
+        for (int i = 0; i < 16; ++i)
+          acc[db][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(racc, acc_voff, acc_soff(db, i), 0));
       }
-      constexpr int lag = 2;
-      const unsigned char* const xb = smem + C::XOFF + (2 * qp) * C::XGROUP + lane * 16 + 2 * C::PB;   // dS^T of group 2 qp + kb
-      const unsigned char* lstage = smem + (C::NSTAGE - lag) * C::STAGE;      // the stage of step it - lag
-      for (int it = 0; it < n_iter + 2; ++it, lstage = next_stage(lstage)) {
-        wait_fills();
-        __syncthreads();
-        fill_next();
-        const int s = it - lag;
-        if (s < 0) continue;
-        const bool act0 = in_span(s, sp0.a0, sp0.b1), act1 = in_span(s, sp1.a0, sp1.b1);
-        if (!act0 && !act1) continue;
-        // acc += dS K: k-step tt of a dS operand covers the block's keys 16 tt .. 16 tt + 15.  A group that was not
-        // active left nothing in its buffer: its operand is zero.
-        bf16x8 bop[2][2];
+    }
+    // These loads must have arrived before the step loop: the compiler, which does not see the fills, would
+    // otherwise wait for them inside the loop with vmcnt(0), and that wait also covers every fill in flight.
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (exclusive && !direct) {
+      const float inv_scale = 1.f / p.scale;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int db = 0; db < C::NCB; ++db)
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            bop[kb][tt] = *reinterpret_cast<const bf16x8*>(xb + kb * C::XGROUP + (s & 1) * C::PB + tt * 1024);
-          }
-        if (!(act0 && act1)) {     // rare (causal edge, tails): kept off the common path
+        for (int i = 0; i < 16; ++i) acc[db][i] *= inv_scale;
+    }
+
+    // ---- the step loop --------------------------------------------------------------------------------------------
+    // Iteration `it` of n_iter + 1.  At its top the wave has waited for all its fills but the newest batch (step it + 1) and
+    // met the others, so the blocks of steps it - 1 and it are in LDS and the stage of step it - 2 is free for step it + 2.
+    // Waves 0..3: A(it) V(it) Q(it).  Waves 4..7: V(it - 1) Q(it - 1) A(it): their scores wait in registers across the barrier.
+    // Each of the three parts exists once in the program and is run or skipped as a whole (variants of the accumulating
+    // part make the register allocator keep copies of the accumulators and move them in every step).
+    f32x16 sacc = zero16(), dpacc = zero16();
+    bf16x8 ds[2] = {};
+    int st_a = 0;                                  // byte offset of the stage of step `it`
+    int st_b = (C::NSTAGE - 1) * C::STAGE;         // ... of step it - 1
+    auto bump = [&](int& s) { s += C::STAGE; if (s == C::NSTAGE * C::STAGE) s = 0; };
+    // A: S^T and dP^T of the step whose blocks are at stage offset `so`
+    auto part_a = [&](int so) {
+      const unsigned char* const sa = smem + so;
+      constexpr int NA = 2 * C::NS;
+      bf16x8 fr[NA];
+      auto req = [&](int z) { fr[z] = *reinterpret_cast<const bf16x8*>(sa + (z & 1) * C::TILE + rowaddr[z / 2]); };   // K (even) / V (odd), k-step z / 2
 #pragma unroll
-          for (int tt = 0; tt < 2; ++tt) {
-            if (!act0) bop[0][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            if (!act1) bop[1][tt] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-          }
-        }
-        constexpr int N = 2 * C::NVA;                              // fragments: (tt, db)
-        bf16x8 fr[N];
+      for (int z = 0; z < C::kAhead; ++z) req(z);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int x = 0; x < N; ++x) {
-          const unsigned char* b0 = lstage + (x / C::NVA) * (16 * DT::row_base(1));
-          fr[x] = tr_read_8(b0 + traddr[0][x % C::NVA], b0 + traddr[1][x % C::NVA]);
-        }
+      for (int z = 0; z < NA; ++z) {
+        if (z & 1) dpacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[z], dof[z / 2], z == 1 ? zero16() : dpacc, 0, 0, 0);
+        else sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[z], qf[z / 2], z == 0 ? zero16() : sacc, 0, 0, 0);
+        if (z + C::kAhead < NA) req(z + C::kAhead);
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int x = 0; x < N; ++x)
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb) {
-            acc[x % C::NVA][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bop[kb][x / C::NVA], fr[x], acc[x % C::NVA][kb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-          }
       }
-      // epilogue: dQ [query x channel] * scale -> accumulator rows (or, in direct mode, the final bf16 rows: half a
-      // line per store)
-      if (direct) {
-        const int out_row_bytes = p.hq * D * 2;
-        const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
-            (void*)(p.dq_out + ((int64_t)(t.q_row0 + 64 * qp) * p.hq + head) * D + 32 * C::NVA * ch), (short)0,
-            n_pair_rows > 0 ? (n_pair_rows - 1) * out_row_bytes + 32 * C::NVA * 2 : 0, 0x00020000);
-        const int out_voff = 4 * g2 * out_row_bytes + 2 * l32;
+    };
+    // V + Q of step sv (its K block at stage offset `so`): P^T = exp2(c S^T - LSE log2 e), masked where the key is past the
+    // block's valid keys or after the row; dS^T = P^T (dP^T - delta); dQ += dS K.  Register i is key 8 (i/4) + 4 g2 + i%4.
+    auto part_vq = [&](int sv, int so) {
+      bf16x8 tf[C::NQ];
+      auto treq = [&](int x) {               // transposed K fragment (tt, db) = (x / NCB, x % NCB)
+        const unsigned char* b0 = smem + so + (x / C::NCB) * (16 * DT::row_base(1));
+        tf[x] = tr_read_8(b0 + traddr[0][x % C::NCB], b0 + traddr[1][x % C::NCB]);
+      };
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+      for (int x = 0; x < C::NQ / 2; ++x) treq(x);     // the first half is on its way during the vector work
+      if (in_span(sv, u0, u1)) {
 #pragma unroll
-          for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const __bf16 val = (__bf16)(acc[db][kb][i] * p.scale);
-              __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rout, out_voff,
-                                                    (32 * kb + 8 * (i / 4) + (i % 4)) * out_row_bytes + 64 * db, 0);
-            }
+        for (int i = 0; i < 16; ++i) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, stat_p));
+          ds[i / 8][i % 8] = (__bf16)(e * (dpacc[i] + stat_d));
+        }
       } else {
+        const bool seg1 = sv >= nt0;
+        const int kt = sv - (seg1 ? nt0 : 0);
+        const int k_pos0 = (seg1 ? kpos1 : kpos0) + kt * C::BK;
+        const int n_valid = min(C::BK, (seg1 ? vis1 : vis0) - kt * C::BK);
+        int hi = min(n_valid, q_lim - k_pos0 + 1) - 4 * g2;     // keys (minus 4 g2) below this bound are seen
+        asm volatile("; masked variant" : "+v"(hi));
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int db = 0; db < C::NVA; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-              const float val = acc[db][kb][i] * p.scale;
-              if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(kb, db, i), 0);
-              else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(kb, db, i), 0);
-            }
+        for (int i = 0; i < 16; ++i) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(sacc[i], p.scale_log2, stat_p));
+          ds[i / 8][i % 8] = (__bf16)((8 * (i / 4) + (i % 4) < hi) ? e * (dpacc[i] + stat_d) : 0.f);
+        }
       }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int x = C::NQ / 2; x < C::NQ; ++x) treq(x);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int x = 0; x < C::NQ; ++x) {
+        acc[x % C::NCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ds[x / C::NCB], tf[x], acc[x % C::NCB], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    for (int it = 0; it <= n_iter; ++it) {
+      wait_fills();
+      __syncthreads();
+      fill_next();
+      const bool do_a = it < n_iter && in_span(it, a0, b1);
+      if (grp == 0 && do_a) part_a(st_a);
+      const int sv = it - grp;
+      if (in_span(sv, a0, b1)) part_vq(sv, grp ? st_b : st_a);
+      if (grp == 1 && do_a) part_a(st_a);
+      bump(st_a);
+      bump(st_b);
+    }
+
+    // epilogue: dQ [query x channel] * scale -> accumulator rows (or, in direct mode, the final bf16 rows: half a
+    // line per store)
+    if (direct) {
+      const int out_row_bytes = p.hq * D * 2;
+      const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
+          (void*)(p.dq_out + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
+          n_wave_rows > 0 ? (n_wave_rows - 1) * out_row_bytes + D * 2 : 0, 0x00020000);
+      const int out_voff = 4 * g2 * out_row_bytes + 2 * l32;
+#pragma unroll
+      for (int db = 0; db < C::NCB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const __bf16 val = (__bf16)(acc[db][i] * p.scale);
+          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rout, out_voff,
+                                                (8 * (i / 4) + (i % 4)) * out_row_bytes + 64 * db, 0);
+        }
+    } else {
+#pragma unroll
+      for (int db = 0; db < C::NCB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const float val = acc[db][i] * p.scale;
+          if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(db, i), 0);
+          else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(db, i), 0);
+        }
     }
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }
@@ -473,8 +412,10 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
     if (rc0 != FCP_OK) return rc0;
     return fcp::launch_schedule(false, fcp::kDqBM, fcp::kDqBN, (int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv, 1, cap_q, region_q, nullptr, 0, st);
   }
+  // dQ units: 128 query rows for two heads of one KV head when the heads pair up, else 256 rows for one head
+  const int head_pair = ((hq / hkv) % 2 == 0) ? 1 : 0;
   int rc = fcp::launch_schedule_bwd((int64_t)hkv * head_dim * 2, q_limit, k_from, work, n_work, cu_seqlens_kv, n_seqs, tq, tkv,
-                                    cap_kv, region_kv, cap_q, region_q, lse, delta, (int64_t)hq * tq, stats, st,
+                                    cap_kv, region_kv, head_pair ? fcp::kDqBM : 2 * fcp::kDqBM, cap_q, region_q, lse, delta, (int64_t)hq * tq, stats, st,
                                     direct ? &rs : nullptr);
   if (rc != FCP_OK) return rc;
 
@@ -505,14 +446,15 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   // dQ over query tiles
   p.hdr = (fcp::SchedHeader*)region_q;
   p.tiles = fcp::sched_tiles(region_q, n_work);
+  const int64_t dq_units = cap_q * (hq / (head_pair ? 2 : 1));
   if (head_dim == 128) {
     static std::atomic<uint64_t> lds_done;
     if ((rc = fcp::raise_lds_limit((const void*)fcp::dq_kernel<128>, fcp::DqCfg<128>::LDS_BYTES, lds_done)) != FCP_OK) return rc;
-    hipLaunchKernelGGL(fcp::dq_kernel<128>, grid_for(cap_q * hq, 1), dim3(768), fcp::DqCfg<128>::LDS_BYTES, st, p);
+    hipLaunchKernelGGL(fcp::dq_kernel<128>, grid_for(dq_units, 1), dim3(512), fcp::DqCfg<128>::LDS_BYTES, st, p, head_pair);
   } else {
     static std::atomic<uint64_t> lds_done;
     if ((rc = fcp::raise_lds_limit((const void*)fcp::dq_kernel<64>, fcp::DqCfg<64>::LDS_BYTES, lds_done)) != FCP_OK) return rc;
-    hipLaunchKernelGGL(fcp::dq_kernel<64>, grid_for(cap_q * hq, 1), dim3(768), fcp::DqCfg<64>::LDS_BYTES, st, p);
+    hipLaunchKernelGGL(fcp::dq_kernel<64>, grid_for(dq_units, 1), dim3(512), fcp::DqCfg<64>::LDS_BYTES, st, p, head_pair);
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;

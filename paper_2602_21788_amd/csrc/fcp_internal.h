@@ -76,7 +76,7 @@ struct Tile { int32_t w[16]; };  // storage type of the list
 
 constexpr int kFwdBM = 256;      // query rows per forward unit
 constexpr int kFwdBN = 64;       // keys per forward inner step
-constexpr int kDqBM = 128;       // query rows per dQ unit
+constexpr int kDqBM = 128;       // query rows per dQ unit (two heads of a KV head), twice that for a single head
 constexpr int kDqBN = 32;        // keys per dQ inner step
 constexpr int kBwdBN = 128;      // keys per dK/dV unit
 constexpr int kBwdBM = 32;       // query rows per dK/dV inner step
@@ -134,11 +134,11 @@ int launch_schedule(bool key_tiles, int32_t tile, int32_t inner, int64_t kv_row_
                     int64_t lse_fill_n, hipStream_t stream, const RowStates* states = nullptr);
 
 // Everything that precedes the backward's attention kernels in one launch: both tile lists (key tiles of kBwdBN
-// keys in region_kv, query tiles of kDqBM rows in region_q) and the row statistics (stats: two planes of n_stats
+// keys in region_kv, query tiles of dq_tile rows in region_q) and the row statistics (stats: two planes of n_stats
 // floats, -LSE log2 e and -delta).
 int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from,
                         const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
-                        int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
+                        int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int32_t dq_tile, int64_t cap_q, void* region_q,
                         const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream,
                         const RowStates* states = nullptr);
 

@@ -646,7 +646,7 @@ int launch_schedule(bool backward, int32_t tile, int32_t inner, int64_t kv_row_b
 
 int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int32_t* k_from,
                         const fcp_work_desc* work, int64_t n_work, const int32_t* cu_seqlens_kv, int32_t n_seqs,
-                        int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int64_t cap_q, void* region_q,
+                        int32_t tq, int32_t tkv, int64_t cap_kv, void* region_kv, int32_t dq_tile, int64_t cap_q, void* region_q,
                         const float* lse, const float* delta, int64_t n_stats, float* stats, hipStream_t stream,
                         const RowStates* states) {
   if (states) { const int rcs = check_row_states(n_work); if (rcs != FCP_OK) return rcs; }
@@ -664,7 +664,7 @@ int launch_schedule_bwd(int64_t kv_row_bytes, const int32_t* q_limit, const int3
   if (stat_blocks < 1) stat_blocks = 1;
   const int state_blocks = states ? row_state_blocks(tq, states->kv_state ? tkv : 0) : 0;
   hipLaunchKernelGGL(sched_bwd_kernel, dim3((unsigned)(2 + stat_blocks + state_blocks)), dim3(kSchedThreads), 0, stream,
-                     job(region_kv, kBwdBN, kBwdBM, cap_kv), job(region_q, kDqBM, kDqBN, cap_q),
+                     job(region_kv, kBwdBN, kBwdBM, cap_kv), job(region_q, dq_tile, kDqBN, cap_q),
                      max_segment_keys(kv_row_bytes), MaskTables{q_limit, k_from}, work,
                      (int32_t)n_work, cu_seqlens_kv, n_seqs, tq, tkv, lse, delta, n_stats, stats, (int)stat_blocks,
                      make_job(states));
