@@ -76,6 +76,8 @@ __global__ __launch_bounds__(1024, 1) void dkv_kernel(const BwdParams p) {
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int role = wave >> 2;                     // 0: P, 1: dV, 2: dS, 3: dK
+  // the producing waves go first at their SIMD's issue port: the accumulating waves' steps wait for what they make
+  if (role == 0 || role == 2) __builtin_amdgcn_s_setprio(2);
   const int pw = wave & 3;                        // key group (and SIMD): keys 32 pw .. 32 pw + 31
   const int l32 = lane & 31, g2 = lane >> 5;
   const int G = p.hq / p.hkv;
