@@ -32,9 +32,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per fcp_attn_bwd_step(_direct) launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload only.
-MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "accumulate"): 5.66e9,
-                              ("packed32k_lognormal24_h32x8_D128", "direct"): 4.65e9}
+# counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload and path only.
+MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "direct"): 4.69e9}
 SEGMENTS = ["fwd_step", "merge", "zero", "delta", "bwd_step", "finalize"]
 
 
