@@ -46,7 +46,8 @@ struct DqCfg {
   static constexpr int STAGE = 2 * TILE;           // K, V
   static constexpr int FILL_AHEAD = 2;             // steps between a block's fill and its first use
   static constexpr int NSTAGE = 2 + FILL_AHEAD;    // one step behind (the second wave group), the step itself, FILL_AHEAD ahead
-  static constexpr int LDS_BYTES = NSTAGE * STAGE;
+  using OUT = RowStage<D>;                         // per wave: the tile's rows on their way out
+  static constexpr int LDS_BYTES = NSTAGE * STAGE + NWAVE * OUT::BYTES;
   static constexpr int NS = D / 16;                // k-steps of one 32 x 32 block of S^T or dP^T
   static constexpr int NCB = D / 32;               // 32-channel blocks of dQ
   static constexpr int TINST = 2 * BK / DT::RPI;   // tile fill instructions per step (K then V)
@@ -116,7 +117,6 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
     const QTile t = read_record<QTile, 12>(s_rec);
     const int head = xcd * heads_here + (unit % units_per_tile) * hpu + (head_pair ? grp : 0);
     const int kvh = head / G;
-    uq.prefetch();
 
     const bool exclusive = (t.flags & kFlagQExclusive) != 0;
     const int rows_here = t.rows;
@@ -185,22 +185,42 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
     }
     auto in_span = [&](int s, int lo_end, int hi_end) { return s >= 0 && (s < lo_end || (s >= nt0 && s < hi_end)); };
 
+    // -LSE log2 e and -delta of the lane's row: asked for first, they arrive while the tiles below are on their way
+    const float stat_p = p.stats[(int64_t)head * p.tq + t.q_row0 + row_ld];
+    const float stat_d = p.stats[(int64_t)p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
     // The first fills go out before the wave's own loads so that their latencies overlap.
 #pragma unroll
     for (int a = 0; a < C::FILL_AHEAD; ++a) fill_next();
-    // own-row fragments, B operands (lane = query column), channels 16 ks + 8 g2 + [0,8): Q and dO
+    // own-row fragments, B operands (lane = query column), channels 16 ks + 8 g2 + [0,8): Q and dO.  Loaded straight
+    // from global memory in that form, every instruction would touch 32 cache lines for 32 bytes of each and a unit's
+    // start would be bound by the rate of the address pipeline (several microseconds for the block's 128 KB); instead
+    // the wave's 32 rows come in whole (LDS-direct fills of four rows each) through its staging area, one tensor after
+    // the other, and the fragments are read from there.  Rows past the tile's last arrive as zeros.
+    const int n_wave_rows = rows_here - wave_r0;                 // rows of the tile from this wave's first on
     bf16x8 qf[C::NS], dof[C::NS];
     {
-      const int64_t off = ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
+      using RT = RowTile<D>;
+      static_assert(RT::bytes(32) <= C::OUT::BYTES, "the staging area holds a 32-row tile");
+      int lane_p = lane;                            // addresses formed here, not ahead of the unit loop (registers)
+      asm volatile("" : "+v"(lane_p));
+      const int q_row_bytes = p.hq * D * 2;
+      const int64_t base = ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D;
+      const int nbytes = n_wave_rows > 0 ? (min(n_wave_rows, 32) - 1) * q_row_bytes + D * 2 : 0;
+      const int area = C::NSTAGE * C::STAGE + wave * C::OUT::BYTES;
+      auto load_tile = [&](const uint16_t* src, bf16x8 (&f)[C::NS]) {
+        const i32x4 r = buffer_rsrc(src + base, nbytes);
 #pragma unroll
-      for (int ks = 0; ks < C::NS; ++ks) {
-        qf[ks] = *reinterpret_cast<const bf16x8*>(p.q + off + 16 * ks);
-        dof[ks] = *reinterpret_cast<const bf16x8*>(p.d_o + off + 16 * ks);
-      }
+        for (int i = 0; i < 32 / RT::RPI; ++i)
+          lds_fill_b128(r, lds0 + area + RT::row_base(RT::RPI * i), fill_voff<RT>(32, 0, i, lane_p, q_row_bytes), 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);         // vmcnt(0)
+#pragma unroll
+        for (int ks = 0; ks < C::NS; ++ks)
+          f[ks] = *reinterpret_cast<const bf16x8*>(smem + area + tile_off<RT>(lane_p & 31, 2 * ks + (lane_p >> 5)));
+        __builtin_amdgcn_s_waitcnt(0xC07F);         // lgkmcnt(0): in registers before the area is filled again
+      };
+      load_tile(p.q, qf);
+      load_tile(p.d_o, dof);
     }
-    // -LSE log2 e and -delta of the lane's row
-    const float stat_p = p.stats[(int64_t)head * p.tq + t.q_row0 + row_ld];
-    const float stat_d = p.stats[(int64_t)p.hq * p.tq + (int64_t)head * p.tq + t.q_row0 + row_ld];
     int q_lim = t.q_pos0 + my_row;                 // last key position the lane's row sees
     if (p.q_limit) q_lim = p.q_limit[t.q_row0 + row_ld];
     // dQ [32-channel block] as [query x channel]: the channel is on the lane, register i is row 8 (i/4) + 4 g2 + i%4 of
@@ -212,7 +232,6 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
     // offset = the rest.
     f32x16 acc[C::NCB];
     const int row_bytes = p.hq * D * 4;
-    const int n_wave_rows = rows_here - wave_r0;                 // rows of the tile from this wave's first on
     const __amdgpu_buffer_rsrc_t racc = __builtin_amdgcn_make_buffer_rsrc(
         (void*)(p.dq + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
         n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 4 : 0, 0x00020000);
@@ -328,31 +347,43 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
       bump(st_b);
     }
 
-    // epilogue: dQ [query x channel] * scale -> accumulator rows (or, in direct mode, the final bf16 rows: half a
-    // line per store)
+    // The next unit's record and the number of the unit after it start their trips here, ahead of the epilogue's
+    // stores: the wave waits for the number (asked for one unit ago) in program order, and after the stores that wait
+    // would last until the last of them has been written.
+    uq.prefetch();
+    // epilogue: dQ [query x channel] * scale -> the final bf16 rows (direct mode) or the accumulator rows; stores of
+    // whole rows through the wave's staging area, atomics straight from the registers
+    unsigned char* const obuf = smem + C::NSTAGE * C::STAGE + wave * C::OUT::BYTES;
+    int lane_e = lane;                              // see RowStage::flush
+    asm volatile("" : "+v"(lane_e));
+    const int l32e = lane_e & 31, g2e = lane_e >> 5;
     if (direct) {
       const int out_row_bytes = p.hq * D * 2;
       const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(p.dq_out + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
           n_wave_rows > 0 ? (n_wave_rows - 1) * out_row_bytes + D * 2 : 0, 0x00020000);
-      const int out_voff = 4 * g2 * out_row_bytes + 2 * l32;
 #pragma unroll
       for (int db = 0; db < C::NCB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const __bf16 val = (__bf16)(acc[db][i] * p.scale);
-          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rout, out_voff,
-                                                (8 * (i / 4) + (i % 4)) * out_row_bytes + 64 * db, 0);
-        }
+        for (int i = 0; i < 16; ++i)
+          C::OUT::put_bf16(obuf, C::OUT::reg_row(i, g2e), 32 * db + l32e, acc[db][i] * p.scale);
+      C::OUT::flush(obuf, lane_e, rout, out_row_bytes, 0);
+    } else if (exclusive) {
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {                 // D / 2 channels per pass
+#pragma unroll
+        for (int db = 0; db < C::NCB / 2; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            C::OUT::put_f32(obuf, C::OUT::reg_row(i, g2e), 32 * db + l32e, acc[h * (C::NCB / 2) + db][i] * p.scale);
+        C::OUT::flush(obuf, lane_e, racc, row_bytes, h * D * 2);
+      }
     } else {
 #pragma unroll
       for (int db = 0; db < C::NCB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float val = acc[db][i] * p.scale;
-          if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(db, i), 0);
-          else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(db, i), 0);
-        }
+        for (int i = 0; i < 16; ++i)
+          __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc[db][i] * p.scale, racc, acc_voff, acc_soff(db, i), 0);
     }
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }

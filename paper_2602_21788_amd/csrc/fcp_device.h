@@ -151,6 +151,58 @@ __device__ inline int fill_voff(int rpw, int wave, int i, int lane, int row_byte
   return row * row_bytes + (((lane % T::CPR) ^ T::key(row)) << 4);
 }
 
+// Wave-private LDS staging for writing a [32 rows x 2 D bytes] tile that the wave holds in the accumulator layout of
+// the 32 x 32 matrix instructions (lane = column inside a 32-column block, register i = row reg_row(i, lane / 32)).
+// Stored from that layout a wave-wide instruction carries 2 or 4 bytes per lane and the memory pipeline takes as long
+// for it as for one of 16 bytes per lane, so a unit's 512 such stores cost several microseconds, which the next unit's
+// first loads then queue behind.  Staged through LDS the same tile leaves in D / 16 instructions of whole rows.
+// The staged row is 2 D bytes: all D channels as bf16, or D / 2 channels as fp32 (two passes).
+template <int D>
+struct RowStage {
+  static constexpr int ROW = 2 * D + 16;           // LDS row stride: the two lane halves (4 rows apart) on different banks
+  static constexpr int BYTES = 32 * ROW;
+  static constexpr int CPR = D / 8;                // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;             // rows per store instruction
+  static constexpr int N = 32 / RPI;
+  // the staged rows are written as 2- and 4-byte values and read back as 16-byte chunks: types that may alias
+  typedef uint16_t __attribute__((may_alias)) u16_any;
+  typedef uint32_t __attribute__((may_alias)) u32_any;
+  typedef u32x4 __attribute__((may_alias)) u32x4_any;
+  __device__ static int reg_row(int i, int g2) { return 8 * (i / 4) + 4 * g2 + (i % 4); }
+  __device__ static int at(int row, int byte) { return row * ROW + byte; }
+  __device__ static void put_bf16(unsigned char* buf, int row, int col, float v) {
+    *reinterpret_cast<u16_any*>(buf + at(row, 2 * col)) = __builtin_bit_cast(uint16_t, (__bf16)v);
+  }
+  __device__ static void put_f32(unsigned char* buf, int row, int col, float v) {
+    *reinterpret_cast<u32_any*>(buf + at(row, 4 * col)) = __builtin_bit_cast(uint32_t, v);
+  }
+  // after the wave has written its staged rows: row r goes to byte offset r * row_bytes + soff0 of the resource
+  // (rows past the resource's range are dropped)
+  __device__ static void flush(const unsigned char* buf, int lane, __amdgpu_buffer_rsrc_t r, int row_bytes, int soff0) {
+    // the lane's addresses are formed here, after the unit's loop: values that the compiler can form ahead of the loop
+    // would hold registers across it
+    asm volatile("" : "+v"(lane));
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int row = lane / CPR, chunk = lane % CPR;
+    const int voff = row * row_bytes + 16 * chunk + soff0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      const u32x4 x = *reinterpret_cast<const u32x4_any*>(buf + at(RPI * j + row, 16 * chunk));
+      __builtin_amdgcn_raw_buffer_store_b128(x, r, voff + RPI * j * row_bytes, 0, 0);
+      // The data registers stay untouched for two more cycles: a 16-byte store followed at once by a vector
+      // instruction that overwrites its first data register has stored the new value now and then (seen with the
+      // row term in the scalar offset; the whole offset is per lane here, the case for which the compiler knows the
+      // hazard, and the wait below does not depend on its table).
+      asm volatile("s_nop 1" :: "v"(x));
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+};
+
 // Unit queue of a persistent block.  Units are numbered per XCD counter; unit u of an XCD is
 // (tile u / per_tile, sub-index u % per_tile).  Wave 0 keeps the atomic for the unit after next
 // and the 64-byte record of the next unit in flight while the block computes the current one,
