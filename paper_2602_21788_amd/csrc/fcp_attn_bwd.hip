@@ -46,8 +46,8 @@ struct DqCfg {
   static constexpr int STAGE = 2 * TILE;           // K, V
   static constexpr int FILL_AHEAD = 2;             // steps between a block's fill and its first use
   static constexpr int NSTAGE = 2 + FILL_AHEAD;    // one step behind (the second wave group), the step itself, FILL_AHEAD ahead
-  using OUT = RowStage<D>;                         // per wave: the tile's rows on their way out
-  static constexpr int LDS_BYTES = NSTAGE * STAGE + NWAVE * OUT::BYTES;
+  static constexpr int AREA = RowTile<D>::bytes(32);   // per wave: its 32 rows of Q, then of dO, on their way in
+  static constexpr int LDS_BYTES = NSTAGE * STAGE + NWAVE * AREA;
   static constexpr int NS = D / 16;                // k-steps of one 32 x 32 block of S^T or dP^T
   static constexpr int NCB = D / 32;               // 32-channel blocks of dQ
   static constexpr int TINST = 2 * BK / DT::RPI;   // tile fill instructions per step (K then V)
@@ -200,13 +200,12 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
     bf16x8 qf[C::NS], dof[C::NS];
     {
       using RT = RowTile<D>;
-      static_assert(RT::bytes(32) <= C::OUT::BYTES, "the staging area holds a 32-row tile");
       int lane_p = lane;                            // addresses formed here, not ahead of the unit loop (registers)
       asm volatile("" : "+v"(lane_p));
       const int q_row_bytes = p.hq * D * 2;
       const int64_t base = ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D;
       const int nbytes = n_wave_rows > 0 ? (min(n_wave_rows, 32) - 1) * q_row_bytes + D * 2 : 0;
-      const int area = C::NSTAGE * C::STAGE + wave * C::OUT::BYTES;
+      const int area = C::NSTAGE * C::STAGE + wave * C::AREA;
       auto load_tile = [&](const uint16_t* src, bf16x8 (&f)[C::NS]) {
         const i32x4 r = buffer_rsrc(src + base, nbytes);
 #pragma unroll
@@ -351,10 +350,10 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
     // stores: the wave waits for the number (asked for one unit ago) in program order, and after the stores that wait
     // would last until the last of them has been written.
     uq.prefetch();
-    // epilogue: dQ [query x channel] * scale -> the final bf16 rows (direct mode) or the accumulator rows; stores of
-    // whole rows through the wave's staging area, atomics straight from the registers
-    unsigned char* const obuf = smem + C::NSTAGE * C::STAGE + wave * C::OUT::BYTES;
-    int lane_e = lane;                              // see RowStage::flush
+    // epilogue: dQ [query x channel] * scale -> accumulator rows (or, in direct mode, the final bf16 rows: half a
+    // line per store).  Staging the tile through LDS for 16-byte stores of whole rows, as the forward kernel does,
+    // measured slower here (+4 % on the packed workload): the narrow stores cost this wave only their issue.
+    int lane_e = lane;                              // addresses formed here, not ahead of the unit's loop (registers)
     asm volatile("" : "+v"(lane_e));
     const int l32e = lane_e & 31, g2e = lane_e >> 5;
     if (direct) {
@@ -362,28 +361,24 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
       const __amdgpu_buffer_rsrc_t rout = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(p.dq_out + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
           n_wave_rows > 0 ? (n_wave_rows - 1) * out_row_bytes + D * 2 : 0, 0x00020000);
+      const int out_voff = 4 * g2e * out_row_bytes + 2 * l32e;
 #pragma unroll
       for (int db = 0; db < C::NCB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          C::OUT::put_bf16(obuf, C::OUT::reg_row(i, g2e), 32 * db + l32e, acc[db][i] * p.scale);
-      C::OUT::flush(obuf, lane_e, rout, out_row_bytes, 0);
-    } else if (exclusive) {
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {                 // D / 2 channels per pass
-#pragma unroll
-        for (int db = 0; db < C::NCB / 2; ++db)
-#pragma unroll
-          for (int i = 0; i < 16; ++i)
-            C::OUT::put_f32(obuf, C::OUT::reg_row(i, g2e), 32 * db + l32e, acc[h * (C::NCB / 2) + db][i] * p.scale);
-        C::OUT::flush(obuf, lane_e, racc, row_bytes, h * D * 2);
-      }
+        for (int i = 0; i < 16; ++i) {
+          const __bf16 val = (__bf16)(acc[db][i] * p.scale);
+          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rout, out_voff,
+                                                (8 * (i / 4) + (i % 4)) * out_row_bytes + 64 * db, 0);
+        }
     } else {
 #pragma unroll
       for (int db = 0; db < C::NCB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc[db][i] * p.scale, racc, acc_voff, acc_soff(db, i), 0);
+        for (int i = 0; i < 16; ++i) {
+          const float val = acc[db][i] * p.scale;
+          if (exclusive) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), racc, acc_voff, acc_soff(db, i), 0);
+          else __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(val, racc, acc_voff, acc_soff(db, i), 0);
+        }
     }
     uq.advance(&s_next_unit, s_rec);   // barrier: the LDS stages are free for the next unit's fills
   }

@@ -135,7 +135,6 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     const QTile t = read_record<QTile, 12>(s_rec);
     const int head = xcd * heads_here + (unit % units_per_tile) * hpu + (p.head_pair ? grp : 0);
     const int kvh = head / G;
-    uq.prefetch();   // next unit's record and the following unit's number start their trips now
 
     const int wave_r0 = (p.head_pair ? (wave & 3) : wave) * 32;
     const bool wave_active = wave_r0 < t.rows;
@@ -202,19 +201,33 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       if (f_dst >= f_dst_end) f_dst -= C::NSTAGE * C::STAGE;
     };
 
+    bf16x8 qf[D / 16];
+    int s_q_area = 0;
     // Prologue fills: tiles 0 and 1.  The previous unit's last barrier guarantees that no wave still reads
     // the stages.
     fill_next();
     fill_next();
 
-    // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16 ks + 8 g2 + [0,8)
-    bf16x8 qf[D / 16];
+    // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16 ks + 8 g2 + [0,8).  Loaded in
+    // that form from global memory an instruction would touch 32 cache lines for 32 bytes of each; instead the wave's
+    // 32 rows come in whole (LDS-direct fills of RPI rows each) beside the first two key tiles, into the part of stages
+    // 2 and 3 that is the wave's own until the first slot's barrier, and the fragments are read from there.  Rows past
+    // the tile's last arrive as zeros.
     {
-      const uint16_t* qp = p.q + ((int64_t)(t.q_row0 + row_ld) * p.hq + head) * D + 8 * g2;
+      using QT = DualTile<D>;
+      static_assert(C::NWAVE * QT::bytes(32) <= 2 * C::STAGE, "the waves' Q tiles fit into two stages");
+      int lane_p = lane;                            // addresses formed here, not ahead of the unit loop (registers)
+      asm volatile("" : "+v"(lane_p));
+      const int q_row_bytes = p.hq * D * 2;
+      const int n_wave_rows = t.rows - wave_r0;
+      const i32x4 rq = buffer_rsrc(p.q + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D,
+                                   n_wave_rows > 0 ? (min(n_wave_rows, 32) - 1) * q_row_bytes + D * 2 : 0);
+      const int area = 2 * C::STAGE + wave * QT::bytes(32);
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+      for (int i = 0; i < 32 / QT::RPI; ++i)
+        lds_fill_b128(rq, lds0 + area + QT::row_base(QT::RPI * i), fill_voff<QT>(32, 0, i, lane_p, q_row_bytes), 0);
+      s_q_area = area;
     }
-
     f32x16 oacc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) oacc[db] = zero16();
@@ -393,6 +406,15 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     // waits for it at the end of its matrix slot it+1, and tile it+2 is first read in matrix slot it+2 of the early
     // waves, which starts after the late waves' matrix slot it+1 has ended with the same wait.
     __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    {
+      using QT = DualTile<D>;
+      int lane_p = lane;
+      asm volatile("" : "+v"(lane_p));
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks)
+        qf[ks] = *reinterpret_cast<const bf16x8*>(smem + s_q_area + tile_off<QT>(lane_p & 31, 2 * ks + (lane_p >> 5)));
+      __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): in registers before anybody fills stage 2
+    }
     __syncthreads();                       // tiles 0 and 1 have landed
     if (grp == 1) __syncthreads();
     for (int it = 0; it <= n_iter; ++it) {
@@ -407,52 +429,56 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       // slot boundary: this wave's fills (issued a step ago) have landed, then everybody meets
       __builtin_amdgcn_s_waitcnt(kWaitVm0);
       __syncthreads();
-      fill_next();
+      if (it + 2 < n_iter) fill_next();      // (nothing in flight when the loop ends: the epilogue reuses the stages)
       if (do_s) vector_slot(it);
       __syncthreads();
     }
     if (grp == 0) __syncthreads();
 
+    // The next unit's record and the number of the unit after it start their trips here, ahead of the epilogue's
+    // stores (waiting for them later must not mean waiting for those stores).
+    uq.prefetch();
     // ---- epilogue: normalise, write partial O (fp32) and LSE --------------------------------
     const float l_tot = lane32_partner_sum(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     scale_rows(inv);
     // Direct mode: the tile's rows get all their keys in this unit, so the normalised O is the final one.
     const bool direct = p.direct && (t.flags & kFlagQExclusive) != 0;
-    if (!direct) {
-      // The rows are reached through a buffer resource that ends with the tile's last row (stores past it are
-      // dropped): per-lane offset = the lane's part (row 4 g2 of a group of eight, channel l32), scalar offset =
-      // the rest.  A store instruction covers two whole 128-byte lines.
+    // The tile leaves as whole rows through the wave's staging area (the stages are free: every wave has passed its
+    // last matrix slot and no fill is in flight); the rows are reached through a buffer resource that ends with the
+    // tile's last row, so that stores past it are dropped.
+    using OUT = RowStage<D>;
+    static_assert(C::NWAVE * OUT::BYTES <= C::LDS_BYTES, "staging areas inside the stages");
+    unsigned char* const obuf = smem + wave * OUT::BYTES;
+    int lane_e = lane;                              // see RowStage::flush
+    asm volatile("" : "+v"(lane_e));
+    const int l32e = lane_e & 31, g2e = lane_e >> 5;
+    const int n_wave_rows = t.rows - wave_r0;
+    if (!direct) {                                  // partial O, fp32: D / 2 channels per pass
       const int row_bytes = p.hq * D * 4;
-      const int n_wave_rows = t.rows - wave_r0;
       const __amdgpu_buffer_rsrc_t ro = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(p.o_part + (int64_t)slot * ((int64_t)p.tq * p.hq * D) + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D),
           (short)0, n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 4 : 0, 0x00020000);
-      const int o_voff = 4 * g2 * row_bytes + 4 * l32;
 #pragma unroll
-      for (int db = 0; db < D / 32; ++db)
+      for (int h = 0; h < 2; ++h) {
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float val = oacc[db][i];   // (a bit cast applied to the vector element itself reads element 0)
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, val), ro, o_voff,
-                                                (8 * (i / 4) + (i % 4)) * row_bytes + 128 * db, 0);
-        }
+        for (int db = 0; db < D / 64; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            OUT::put_f32(obuf, OUT::reg_row(i, g2e), 32 * db + l32e, oacc[h * (D / 64) + db][i]);
+        OUT::flush(obuf, lane_e, ro, row_bytes, h * D * 2);
+      }
     }
-    if (p.o_out && (p.running || direct)) {   // the final rows as bf16 (half a line per store)
+    if (p.o_out && (p.running || direct)) {   // the final rows as bf16
       const int row_bytes = p.hq * D * 2;
-      const int n_wave_rows = t.rows - wave_r0;
       const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
           (void*)(p.o_out + ((int64_t)(t.q_row0 + wave_r0) * p.hq + head) * D), (short)0,
           n_wave_rows > 0 ? (n_wave_rows - 1) * row_bytes + D * 2 : 0, 0x00020000);
-      const int o_voff = 4 * g2 * row_bytes + 2 * l32;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const __bf16 val = (__bf16)oacc[db][i];
-          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(short, val), rb, o_voff,
-                                                (8 * (i / 4) + (i % 4)) * row_bytes + 64 * db, 0);
-        }
+        for (int i = 0; i < 16; ++i) OUT::put_bf16(obuf, OUT::reg_row(i, g2e), 32 * db + l32e, oacc[db][i]);
+      OUT::flush(obuf, lane_e, rb, row_bytes, 0);
     }
     if (row_valid && g2 == 0) {
       const float lse = l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;

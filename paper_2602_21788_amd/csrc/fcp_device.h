@@ -187,15 +187,17 @@ struct RowStage {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int row = lane / CPR, chunk = lane % CPR;
     const int voff = row * row_bytes + 16 * chunk + soff0;
+    u32x4 x[N];                                    // all chunks first: one LDS latency, not N
+#pragma unroll
+    for (int j = 0; j < N; ++j) x[j] = *reinterpret_cast<const u32x4_any*>(buf + at(RPI * j + row, 16 * chunk));
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-      const u32x4 x = *reinterpret_cast<const u32x4_any*>(buf + at(RPI * j + row, 16 * chunk));
-      __builtin_amdgcn_raw_buffer_store_b128(x, r, voff + RPI * j * row_bytes, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b128(x[j], r, voff + RPI * j * row_bytes, 0, 0);
       // The data registers stay untouched for two more cycles: a 16-byte store followed at once by a vector
       // instruction that overwrites its first data register has stored the new value now and then (seen with the
       // row term in the scalar offset; the whole offset is per lane here, the case for which the compiler knows the
       // hazard, and the wait below does not depend on its table).
-      asm volatile("s_nop 1" :: "v"(x));
+      asm volatile("s_nop 1" :: "v"(x[j]));
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
