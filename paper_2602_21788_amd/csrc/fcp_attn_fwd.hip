@@ -20,7 +20,7 @@
 //     holds 16 keys of ONE query column, so the row maximum and sum are in-lane reductions
 //     plus a single exchange with the lane 32 away, and the exponentiated scores are already
 //     in the A-operand layout of the second contraction O += P V, whose accumulator is then
-//     [query x channel] with the channel on the lane: the epilogue stores whole 128-byte lines;
+//     [query x channel] with the channel on the lane; the epilogue stages the wave's tile in LDS and stores whole rows;
 //   * PING-PONG: waves w and w+4 share a SIMD (measured).  Matrix and vector instructions of
 //     DIFFERENT waves of a SIMD execute together almost perfectly, those of one wave hardly do.
 //     Each wave therefore alternates a matrix slot (scores of tile t, O += P V of tile t-1)
@@ -176,8 +176,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
       rv[s] = buffer_rsrc(p.v + off, bytes);
     }
     // This wave's share (RPW rows of K and of V, FILLS instructions) of the LDS-direct fill of the NEXT tile in
-    // list order into the next stage (tiles are filled strictly in order 0, 1, 2, ...).  Tiles past the end of
-    // the list lie outside the resource's range, load nothing and write zeros.  The running
+    // list order into the next stage (tiles are filled strictly in order 0, 1, 2, ...).  A prologue fill past the end of
+    // a one-tile list lies outside the resource's range, loads nothing and writes zeros; the loop issues none.  The running
     // state keeps the scalar work per call small.
     i32x4 f_rk = rk[0], f_rv = rv[0];
     int f_left = nt0;                      // tiles left in segment 0 while it is being filled
