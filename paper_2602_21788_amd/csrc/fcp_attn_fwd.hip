@@ -203,9 +203,8 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
 
     bf16x8 qf[D / 16];
     int s_q_area = 0;
-    // Prologue fills: tiles 0 and 1.  The previous unit's last barrier guarantees that no wave still reads
-    // the stages.
-    fill_next();
+    // Prologue fills: tile 0, the wave's Q rows, tile 1 - in the order they are needed: the first slot starts when
+    // all but tile 1 have landed.  The previous unit's last barrier guarantees that no wave still reads the stages.
     fill_next();
 
     // Q fragments: B operand of S^T = K Q^T.  Lane holds column q = l32, channels 16 ks + 8 g2 + [0,8).  Loaded in
@@ -228,6 +227,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
         lds_fill_b128(rq, lds0 + area + QT::row_base(QT::RPI * i), fill_voff<QT>(32, 0, i, lane_p, q_row_bytes), 0);
       s_q_area = area;
     }
+    fill_next();
     f32x16 oacc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) oacc[db] = zero16();
@@ -405,7 +405,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
     // whose previous tile it-2 was last read in matrix slot it-1 of both halves, two and one slots earlier; a wave
     // waits for it at the end of its matrix slot it+1, and tile it+2 is first read in matrix slot it+2 of the early
     // waves, which starts after the late waves' matrix slot it+1 has ended with the same wait.
-    __builtin_amdgcn_s_waitcnt(kWaitVm0);
+    __builtin_amdgcn_s_waitcnt(kWaitVm0 | C::FILLS);   // everything but this wave's part of tile 1 (the newest loads)
     {
       using QT = DualTile<D>;
       int lane_p = lane;
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(512, 1) void fwd_kernel(const FwdParams p) {
         qf[ks] = *reinterpret_cast<const bf16x8*>(smem + s_q_area + tile_off<QT>(lane_p & 31, 2 * ks + (lane_p >> 5)));
       __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): in registers before anybody fills stage 2
     }
-    __syncthreads();                       // tiles 0 and 1 have landed
+    __syncthreads();                       // tile 0 has landed (tile 1: by the first slot boundary)
     if (grp == 1) __syncthreads();
     for (int it = 0; it <= n_iter; ++it) {
       const bool do_s = it < n_w, do_pv = it > 0 && it - 1 < n_w;
