@@ -176,11 +176,33 @@ __device__ inline void block_running_max(uint64_t v0, uint64_t v1, uint64_t* s_w
   before1 = before0 > v0 ? before0 : v0;        // ... before v1
 }
 
+constexpr int kSmallList = 64;   // up to this many items the flags come from a comparison of all pairs
+
 __device__ inline void exclusive_flags_all(const int32_t (*rng)[7], int32_t n_work, uint64_t* key, uint64_t* s_wmax, int32_t* fl) {
   const int tid = threadIdx.x;
   constexpr uint64_t kNone = ~(uint64_t)0;
   for (int32_t i = tid; i < n_work; i += kSchedThreads)
     fl[i] = rng[i][0] < 0 ? 0 : (kFlagQExclusive | kFlagSeg0Exclusive | kFlagSeg1Exclusive);
+  if (n_work <= kSmallList) {
+    // Short lists (a packed micro-batch of a few dozen sequences): all pairs of segment slots, 16 or fewer per thread -
+    // the two sorts below are 36 or more rounds of LDS traffic and block barriers, 10 us where this takes 1.  The same
+    // rules: empty segments and invalid items take no part, sequences compare by their low 21 bits, an item's own
+    // other segment counts, query rows are compared once per pair of items.
+    __syncthreads();
+    const int32_t m = 2 * n_work;
+    for (int32_t idx = tid; idx < m * m; idx += kSchedThreads) {
+      const int32_t a = idx / m, b = idx - a * m;
+      if (a == b) continue;
+      const int32_t ia = a >> 1, sa = a & 1, ib = b >> 1, sb = b & 1;
+      if (rng[ia][0] < 0 || rng[ib][0] < 0) continue;
+      const int32_t a0 = rng[ia][3 + 2 * sa], a1 = rng[ia][4 + 2 * sa], b0 = rng[ib][3 + 2 * sb], b1 = rng[ib][4 + 2 * sb];
+      if (a1 > a0 && b1 > b0 && ((rng[ia][0] ^ rng[ib][0]) & 0x1FFFFF) == 0 && a0 < b1 && b0 < a1)
+        atomicAnd(&fl[ia], ~(sa ? kFlagSeg1Exclusive : kFlagSeg0Exclusive));
+      if (sa == 0 && sb == 0 && rng[ia][1] < rng[ib][2] && rng[ib][1] < rng[ia][2]) atomicAnd(&fl[ia], ~kFlagQExclusive);
+    }
+    __syncthreads();
+    return;
+  }
   // ---- query rows: key = start << 11 | item
   int32_t np = 2;
   while (np < n_work) np <<= 1;
