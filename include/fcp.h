@@ -190,7 +190,8 @@ int fcp_attn_bwd_delta(const void* o, const void* d_o, int32_t tq, int32_t hq, i
  * [tkv,hkv,D].  Rows (keys) that only one work item of the call touches are read, added to and
  * written back with plain loads and stores; the others use fp32 atomics, so their summation
  * order varies run to run.  While the call runs nobody else may write the accumulators.
- * Limits: tq*hq*head_dim and tkv*hkv*head_dim below 2^29 elements, n_work <= 2^24 items (FCP_ERR_UNSUPPORTED).
+ * Limits: tq*hq*head_dim below 2^30 - 2^21 elements (the bf16 rows of a work item are addressed with 32-bit byte
+ * offsets), n_work <= 2^24 items (FCP_ERR_UNSUPPORTED).
  * Other arguments as in fcp_attn_fwd_step; scratch sized with FCP_SCRATCH_BWD.
  */
 int fcp_attn_bwd_step(const void* q, const void* k, const void* v, const void* d_o,

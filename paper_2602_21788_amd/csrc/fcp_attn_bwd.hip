@@ -416,9 +416,11 @@ static int bwd_step(const void* q, const void* k, const void* v, const void* d_o
   const size_t need = fcp_scratch_bytes(FCP_SCRATCH_BWD, tq, tkv, hq, hkv, head_dim, n_work, 1);
   if (scratch_bytes < need) return fail(FCP_ERR_CAPACITY, "fcp_attn_bwd_step: scratch %zu < %zu bytes", scratch_bytes, need);
 
-  // (32-bit byte offsets into Q / dO / dQ and the pool, advanced a few blocks past the end by the fills)
-  if ((int64_t)tq * hq * head_dim * 4 >= ((int64_t)1 << 31) || (int64_t)tkv * hkv * head_dim * 4 >= ((int64_t)1 << 31))
-    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim and tkv * hkv * head_dim must stay below 2^29 elements");
+  // The Q / dO rows of a work item are reached through one buffer resource with 32-bit byte offsets, which the fills
+  // advance a few blocks past the item's end; an item has at most tq rows.  (The accumulators and outputs are reached
+  // tile by tile, the pool segment by segment: the scheduler bounds a segment.)
+  if ((int64_t)tq * hq * head_dim * 2 + ((int64_t)1 << 22) >= ((int64_t)1 << 31))
+    return fail(FCP_ERR_UNSUPPORTED, "fcp_attn_bwd_step: tq * hq * head_dim must stay below 2^30 - 2^21 elements");
   hipStream_t st = (hipStream_t)stream;
   const int64_t cap_kv = fcp::kv_tile_cap(tkv, n_work);
   const int64_t cap_q = fcp::q_tile_cap(tq, tkv, n_work, 1 << 20);

@@ -61,9 +61,10 @@ def _run_both(ra):
 
 
 def full_size_sampled(cfg, kv_heads, stride, tail_keys=300):
+    """cfg: index into the five workloads, or a Workload"""
     import torch
     from paper_2602_21788_amd.rank import RankAttention
-    wl = synth.make_workload(cfg)
+    wl = cfg if isinstance(cfg, synth.Workload) else synth.make_workload(cfg)
     q, k, v, do = synth.draw_qkvdo(wl)
     cu = wl.cu_seqlens
     G = wl.hq // wl.hkv
@@ -166,3 +167,11 @@ def test_cfg2_packed32k_rank0_full_size_both_families_against_the_oracle():
     """The benchmark workload: the direct entry points (what bench.py times) and the plain ones, each against the
     oracle on sampled rows, the tail keys and - through the sparse-dO run - every key of one KV head."""
     full_size_sampled(2, kv_heads=(2,), stride=31)
+
+
+def test_one_131072_token_sequence_unsharded_32_heads_largest_rank_the_backward_accepts():
+    """131072 rows x 32 heads x 128 on one rank (2^29 elements per tensor, 1 GiB of bf16 each: the bf16 rows of the one
+    work item span 2^30 bytes, the largest 32-bit offsets the kernels form; 2 GiB fp32 accumulators and partial O), one
+    1024-tile work item per list."""
+    wl = synth.custom_workload([131072], [1], 32, 8, 128, rank=0, seed=11, name="L131072_d1_h32x8_D128")
+    full_size_sampled(wl, kv_heads=(5,), stride=997, tail_keys=200)

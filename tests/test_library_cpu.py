@@ -89,6 +89,11 @@ def test_device_entry_points_reject_bad_arguments_on_host():
     assert L.fcp_attn_fwd_step(fake, fake, fake, fake, 1, fake, 1, 1, 8, 8, 4, 4, 128, -1.0, fake, fake, fake, 1 << 20, None) == B.FCP_ERR_INVALID_ARG
     assert L.fcp_attn_bwd_step(fake, fake, fake, fake, fake, fake, fake, 1, fake, 1, 8, 8, 4, 4, 32, 0.1, fake, fake, fake, fake, 1 << 20, None) == B.FCP_ERR_UNSUPPORTED
     assert L.fcp_attn_bwd_step(fake, fake, fake, fake, None, fake, fake, 1, fake, 1, 8, 8, 4, 4, 128, 0.1, fake, fake, fake, fake, 1 << 20, None) == B.FCP_ERR_INVALID_ARG
+    # a rank whose bf16 Q rows pass 2^31 bytes (32-bit offsets inside a work item) is refused, one just below is not
+    # refused for its size (it fails later, on the scratch size given here)
+    assert L.fcp_attn_bwd_step(fake, fake, fake, fake, fake, fake, fake, 1, fake, 1, 1 << 18, 1 << 18, 32, 8, 128, 0.1, fake, fake, fake, fake, 1 << 40, None) == B.FCP_ERR_UNSUPPORTED
+    assert b"2^30" in L.fcp_last_error()
+    assert L.fcp_attn_bwd_step(fake, fake, fake, fake, fake, fake, fake, 1, fake, 1, 1 << 17, 1 << 17, 32, 8, 128, 0.1, fake, fake, fake, fake, 8, None) == B.FCP_ERR_CAPACITY
     assert L.fcp_lse_merge(fake, fake, 17, 8, 4, 128, fake, fake, None) == B.FCP_ERR_UNSUPPORTED
     assert L.fcp_lse_merge(fake, fake, 0, 8, 4, 128, fake, fake, None) == B.FCP_ERR_INVALID_ARG
     assert L.fcp_attn_bwd_delta(fake, None, 8, 4, 128, fake, None) == B.FCP_ERR_INVALID_ARG
