@@ -22,11 +22,16 @@
 //   V  P^T = exp2(c S^T - LSE log2 e) with the mask, dS^T = P^T o (dP^T - delta), bf16, in registers in the A-operand form of
 //   Q  dQ += dS K [query x channel] (K^T by transpose reads).
 // A single wave issues about one instruction every six cycles whatever its kind, so the vector work of one wave has to
-// meet the matrix work of ANOTHER wave of its SIMD: waves w and w + 4 share a SIMD, and the second group runs its steps
-// shifted - between two barriers waves 0..3 do A V Q of step `it`, waves 4..7 do V Q of step it - 1 and then A of step
-// `it` - so that one of the two is in its contraction while the other exponentiates.
-// (The role-split predecessor of this kernel - P, dS and dQ waves exchanging bf16 tiles through LDS, 12 waves - spent
-// its steps in the hand-over chain barrier -> LDS -> matrix -> exponentials -> LDS -> barrier.)
+// meet the matrix work of ANOTHER wave of its SIMD: waves w and w + 4 share a SIMD, and a step is two slots, as in the
+// forward kernel - a matrix slot (Q of step it - 1, its transposed fragments requested before the slot's barrier, then
+// A of step it: 24 matrix instructions back to back, at raised priority) and a vector slot (V of step it); waves 4..7
+// run one slot behind waves 0..3 (one barrier more at the start of a unit, one less at its end), so that the matrix
+// slot of one wave meets the vector slot of the other.
+// (Two predecessors: a role-split kernel - P, dS and dQ waves exchanging bf16 tiles through LDS, 12 waves - spent its
+// steps in the hand-over chain barrier -> LDS -> matrix -> exponentials -> LDS -> barrier; the same independent waves
+// with ONE barrier per step and the second group's parts merely reordered (V Q of step it - 1, then A of step it) left
+// the two waves of a SIMD competing for the matrix pipe in one phase and idle at the barrier in another: 7 % slower
+// on a 16384-token sequence, 4 % on the packed workload.)
 // The result is added to the caller's fp32 accumulator once per unit: with plain
 // load-add-store when the scheduler found that no other item of the launch touches the same rows (always the
 // case for degree-1 sequences), otherwise with fp32 atomics.
@@ -259,15 +264,13 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
     }
 
     // ---- the step loop --------------------------------------------------------------------------------------------
-    // Iteration `it` of n_iter + 1.  At its top the wave has waited for all its fills but the newest batch (step it + 1) and
-    // met the others, so the blocks of steps it - 1 and it are in LDS and the stage of step it - 2 is free for step it + 2.
-    // Waves 0..3: A(it) V(it) Q(it).  Waves 4..7: V(it - 1) Q(it - 1) A(it): their scores wait in registers across the barrier.
+    // Iteration `it` of n_iter + 1, two slots.  Before the first barrier the wave has waited for all its fills but the
+    // newest batch (step it + 1), so after it the blocks of steps it - 1 and it are in LDS and the stage of step it - 2 is
+    // free for step it + 2.  Matrix slot: Q(it - 1), A(it).  Vector slot: V(it), whose dS waits in registers for the next
+    // matrix slot.  Waves 4..7 pass every barrier one slot later than waves 0..3, so they wait for their fills once more
+    // before the second barrier: the waves 0..3 read the block of step it + 1 right after it.
     // Each of the three parts exists once in the program and is run or skipped as a whole (variants of the accumulating
     // part make the register allocator keep copies of the accumulators and move them in every step).
-    // A wave runs at raised priority except inside its runs of matrix instructions: where the two waves of a SIMD
-    // compete for the issue port, the one in its vector work goes first - the other's matrix instruction is wanted
-    // only every 32 cycles, while the vector work is what the next matrix run waits for (measured: -4.5 %; the
-    // opposite choice and a fixed preference for either group are slower than none).
     f32x16 sacc = zero16(), dpacc = zero16();
     bf16x8 ds[2] = {};
     int st_a = 0;                                  // byte offset of the stage of step `it`
@@ -281,7 +284,6 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
       auto req = [&](int z) { fr[z] = *reinterpret_cast<const bf16x8*>(sa + (z & 1) * C::TILE + rowaddr[z / 2]); };   // K (even) / V (odd), k-step z / 2
 #pragma unroll
       for (int z = 0; z < C::kAhead; ++z) req(z);
-      __builtin_amdgcn_s_setprio(0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int z = 0; z < NA; ++z) {
@@ -290,18 +292,10 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
         if (z + C::kAhead < NA) req(z + C::kAhead);
         __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_s_setprio(2);
     };
-    // V + Q of step sv (its K block at stage offset `so`): P^T = exp2(c S^T - LSE log2 e), masked where the key is past the
-    // block's valid keys or after the row; dS^T = P^T (dP^T - delta); dQ += dS K.  Register i is key 8 (i/4) + 4 g2 + i%4.
-    auto part_vq = [&](int sv, int so) {
-      bf16x8 tf[C::NQ];
-      auto treq = [&](int x) {               // transposed K fragment (tt, db) = (x / NCB, x % NCB)
-        const unsigned char* b0 = smem + so + (x / C::NCB) * (16 * DT::row_base(1));
-        tf[x] = tr_read_8(b0 + traddr[0][x % C::NCB], b0 + traddr[1][x % C::NCB]);
-      };
-#pragma unroll
-      for (int x = 0; x < C::NQ / 2; ++x) treq(x);     // the first half is on its way during the vector work
+    // The vector part of step sv: P^T = exp2(c S^T - LSE log2 e), masked where the key is past the block's valid keys
+    // or after the row; dS^T = P^T (dP^T - delta).  Register i is key 8 (i/4) + 4 g2 + i%4.
+    auto part_v = [&](int sv) {
       if (in_span(sv, u0, u1)) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
@@ -321,30 +315,44 @@ __global__ __launch_bounds__(512, 1) void dq_kernel(const BwdParams p, const int
           ds[i / 8][i % 8] = (__bf16)((8 * (i / 4) + (i % 4) < hi) ? e * (dpacc[i] + stat_d) : 0.f);
         }
       }
-      __builtin_amdgcn_sched_barrier(0);
+    };
+    // The transposed K fragments of the block at stage offset `so` (fragment (tt, db) = (x / NCB, x % NCB)) and the
+    // accumulation dQ += dS K that uses them.
+    bf16x8 tf[C::NQ] = {};
+    auto tr_request = [&](int so) {
 #pragma unroll
-      for (int x = C::NQ / 2; x < C::NQ; ++x) treq(x);
-      __builtin_amdgcn_s_setprio(0);
+      for (int x = 0; x < C::NQ; ++x) {
+        const unsigned char* b0 = smem + so + (x / C::NCB) * (16 * DT::row_base(1));
+        tf[x] = tr_read_8(b0 + traddr[0][x % C::NCB], b0 + traddr[1][x % C::NCB]);
+      }
+    };
+    auto part_q = [&]() {
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int x = 0; x < C::NQ; ++x) {
         acc[x % C::NCB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ds[x / C::NCB], tf[x], acc[x % C::NCB], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_s_setprio(2);
     };
+    if (grp == 1) __syncthreads();
     for (int it = 0; it <= n_iter; ++it) {
+      const bool q_on = in_span(it - 1, a0, b1);
+      const bool a_on = it < n_iter && in_span(it, a0, b1);
+      if (q_on) tr_request(st_b);
       wait_fills();
       __syncthreads();
       fill_next();
-      const bool do_a = it < n_iter && in_span(it, a0, b1);
-      if (grp == 0 && do_a) part_a(st_a);
-      const int sv = it - grp;
-      if (in_span(sv, a0, b1)) part_vq(sv, grp ? st_b : st_a);
-      if (grp == 1 && do_a) part_a(st_a);
+      __builtin_amdgcn_s_setprio(3);   // the matrix stream goes first at the SIMD's issue port (as in the forward kernel)
+      if (q_on) part_q();
+      if (a_on) part_a(st_a);
+      __builtin_amdgcn_s_setprio(0);
+      wait_fills();
+      __syncthreads();
+      if (a_on) part_v(it);
       bump(st_a);
       bump(st_b);
     }
+    if (grp == 0) __syncthreads();
 
     // The next unit's record and the number of the unit after it start their trips here, ahead of the epilogue's
     // stores: the wave waits for the number (asked for one unit ago) in program order, and after the stores that wait
