@@ -58,7 +58,7 @@ struct DqCfg {
   static constexpr int TINST = 2 * BK / DT::RPI;   // tile fill instructions per step (K then V)
   static constexpr int IPW = TINST / NWAVE;        // ... per wave: waves 0..3 fill K, waves 4..7 fill V
   static constexpr int NQ = 2 * NCB;               // matrix instructions of a step's accumulation
-  static constexpr int kAhead = 6;                 // row fragments requested this many matrix instructions ahead
+  static constexpr int kAhead = 4;                 // row fragments requested this many matrix instructions ahead (6: registers spill)
   static_assert(IPW * NWAVE == TINST && IPW >= 1, "fill split");
   static_assert(BK == 32, "one 32 x 32 score block per wave and step");
 };
