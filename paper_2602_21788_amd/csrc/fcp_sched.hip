@@ -146,6 +146,11 @@ __device__ inline void stage_item(int32_t (&r)[7], const fcp_work_desc& a, bool 
 // are treated as one, which can only clear a flag that could have been set (the safe side).
 // `key`: LDS work area of 2 * kMaxExclusiveScan entries; `fl`: LDS, one word per item, written here.
 __device__ inline void bitonic_sort(uint64_t* key, int32_t n_pow2) {
+  // A list written in row order (the usual case: items by sequence, chunks by position) is sorted already: one pass
+  // over the neighbours finds that out, and the log^2 rounds of exchanges and block barriers are skipped.
+  int ordered = 1;
+  for (int32_t t = threadIdx.x; t + 1 < n_pow2; t += kSchedThreads) ordered &= key[t] <= key[t + 1];
+  if (__syncthreads_and(ordered)) return;
   for (int32_t k = 2; k <= n_pow2; k <<= 1)
     for (int32_t j = k >> 1; j > 0; j >>= 1) {
       for (int32_t t = threadIdx.x; t < n_pow2 / 2; t += kSchedThreads) {
@@ -479,35 +484,48 @@ __device__ void row_states(
   }
   __syncthreads();
 
-  // Each block takes one contiguous share of the rows (query rows, then pool rows) and first picks the items that reach
-  // into it; for many short sequences that is a small part of the list.  Then one LANE per row: every lane walks the
-  // picked items (all lanes read the same item, an LDS broadcast), so a wave classifies 64 rows in one pass and nothing
-  // is exchanged between lanes.  Rows that are accumulated into are then cleared by the whole wave, one after the other.
-  // (Every row against every item is rows x items tests: 0.36 ms for 256 K rows and 1000 items, however arranged.)
+  // Rows are taken in batches of 64, one LANE per row.  Batch f belongs to block f mod count, so every block's batches
+  // are spread evenly over all rows: any run of rows that must be cleared is shared by all blocks, and a block still
+  // meets only the items that reach into one of its batches (for many short sequences a small part of the list),
+  // which it picks first.  A wave then walks the picked items for its 64 rows (all lanes read the same item, an LDS
+  // broadcast; nothing is exchanged between lanes).  The rows that are accumulated into go to a list in LDS, and the
+  // block's 16 waves clear them in turn.  (Every row against every item, one wave per row and a search of cu_seqlens
+  // per pool row, took 0.33 ms for 256 K rows and 1000 items.)
   const int64_t n_rows = (int64_t)tq + n_kv_rows;     // (the forward classifies its query rows only)
-  const int64_t share = ((n_rows + count - 1) / count + 63) & ~(int64_t)63;
-  const int64_t row_lo = (int64_t)(blockIdx.x - first) * share;
-  const int64_t row_hi = row_lo + share < n_rows ? row_lo + share : n_rows;
-  int32_t* s_pick = reinterpret_cast<int32_t*>(area->key);      // free again once the flags are known
-  int32_t& n_pick = *reinterpret_cast<int32_t*>(&area->wmax[0]);
-  if (tid == 0) n_pick = 0;
+  const int64_t n_batches = (n_rows + 63) >> 6;
+  const int64_t blk = blockIdx.x - first;
+  const int wave = tid >> 6;
+  int32_t* s_pick = reinterpret_cast<int32_t*>(area->key);                       // free again once the flags are known
+  int64_t* s_clear = reinterpret_cast<int64_t*>(area->key + kMaxExclusiveScan);  // kSchedThreads rows at most
+  int32_t* s_cnt = reinterpret_cast<int32_t*>(&area->wmax[0]);                   // [0] items picked, [1] rows to clear
+  if (tid == 0) s_cnt[0] = 0;
   __syncthreads();
   {
-    // the share as query rows [qa, qb) and pool rows [ka, kb); either may be empty
-    const int64_t qa = row_lo, qb = row_hi < tq ? row_hi : (int64_t)tq;
-    const int64_t ka = (row_lo > tq ? row_lo : (int64_t)tq) - tq, kb = row_hi - tq;
+    // does the range of rows [s, e) meet a batch of this block?  The first batch at or after s / 64 that is ours.
+    auto mine = [&](int64_t s0, int64_t e0) {
+      if (e0 <= s0) return false;
+      const int64_t fs = s0 >> 6;
+      int64_t d = (blk - fs) % count;
+      if (d < 0) d += count;
+      return ((fs + d) << 6) < e0;
+    };
     for (int32_t i = tid; i < n_work; i += kSchedThreads) {
-      const bool q = s_rng[i][1] < qb && qa < s_rng[i][2];          // (a rejected item has empty ranges)
-      const bool k0 = s_rng[i][3] < kb && ka < s_rng[i][4] && n_kv_rows > 0;
-      const bool k1 = s_rng[i][5] < kb && ka < s_rng[i][6] && n_kv_rows > 0;
-      if (q || k0 || k1) s_pick[atomicAdd(&n_pick, 1)] = i;
+      bool hit = mine(s_rng[i][1], s_rng[i][2]);                                 // (a rejected item has empty ranges)
+      if (n_kv_rows > 0)
+        hit = hit || mine((int64_t)tq + s_rng[i][3], (int64_t)tq + s_rng[i][4]) ||
+              mine((int64_t)tq + s_rng[i][5], (int64_t)tq + s_rng[i][6]);
+      if (hit) s_pick[atomicAdd(&s_cnt[0], 1)] = i;
     }
   }
   __syncthreads();
-  const int32_t n_cand = n_pick;
+  const int32_t n_cand = s_cnt[0];
   const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int64_t r0 = row_lo + (tid >> 6) * 64; r0 < row_hi; r0 += kSchedThreads) {
-    const int64_t r = r0 + lane;
+  const int64_t per_round = (int64_t)count * (kSchedThreads / 64);
+  for (int64_t f0 = 0; f0 < n_batches; f0 += per_round) {    // the same trip count for every wave of the block
+    if (tid == 0) s_cnt[1] = 0;
+    const int64_t f = f0 + (int64_t)wave * count + blk;
+    const int64_t r0 = f << 6, r = r0 + lane;
+    const bool live = r < n_rows;
     int32_t cnt = 0, own = 0;            // covering (item, segment) pairs; flags bit of the last one found
     // (no branch inside these loops: the reads of several items are in flight together)
     if (r0 + 63 < tq) {                  // 64 query rows
@@ -519,34 +537,42 @@ __device__ void row_states(
         cnt += hit;
         own = hit ? s_fl[j] & kFlagQExclusive : own;
       }
-    } else {                             // pool rows, or the batch with the last query rows and the first pool rows
+    } else if (r0 < n_rows) {            // pool rows, or the batch with the last query rows and the first pool rows
       const bool is_q = r < tq;
       const int32_t x = (int32_t)(is_q ? r : r - tq);
 #pragma unroll 4
       for (int32_t c = 0; c < n_cand; ++c) {
         const int32_t j = s_pick[c];
-        const int32_t f = s_fl[j];
+        const int32_t fj = s_fl[j];
         const bool hq = is_q && s_rng[j][1] <= x && x < s_rng[j][2];
         const bool h0 = !is_q && s_rng[j][3] <= x && x < s_rng[j][4];
         const bool h1 = !is_q && s_rng[j][5] <= x && x < s_rng[j][6];
         cnt += (int)hq + (int)h0 + (int)h1;
-        own = hq ? f & kFlagQExclusive : own;
-        own = h0 ? f & kFlagSeg0Exclusive : own;
-        own = h1 ? f & kFlagSeg1Exclusive : own;
+        own = hq ? fj & kFlagQExclusive : own;
+        own = h0 ? fj & kFlagSeg0Exclusive : own;
+        own = h1 ? fj & kFlagSeg1Exclusive : own;
       }
     }
     const int state = cnt == 0 ? 0 : (cnt == 1 && own != 0) ? 2 : 1;
-    const bool live = r < row_hi;
     if (live) {
       if (r < tq) q_state[r] = (uint8_t)state;
       else kv_state[r - tq] = (uint8_t)state;
     }
-    // clearing: the wave takes the batch's accumulated rows one by one
-    uint64_t todo = __builtin_amdgcn_ballot_w64(live && state == 1 && (r < tq ? dq_acc != nullptr : true));
-    while (todo) {
-      const int l = __builtin_ctzll(todo);
-      todo &= todo - 1;
-      const int64_t rr = r0 + l;
+    __syncthreads();
+    const bool clear = live && state == 1 && (r >= tq || dq_acc != nullptr);
+    const uint64_t todo = __builtin_amdgcn_ballot_w64(clear);
+    if (todo) {
+      int32_t base = 0;
+      if (lane == 0) base = atomicAdd(&s_cnt[1], __builtin_popcountll(todo));
+      base = __builtin_amdgcn_readfirstlane(base);
+      const int32_t pos = base + (int32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(todo >> 32),
+                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)todo, 0));
+      if (clear) s_clear[pos] = r;
+    }
+    __syncthreads();
+    const int32_t n_clear = s_cnt[1];
+    for (int32_t c = wave; c < n_clear; c += kSchedThreads / 64) {
+      const int64_t rr = s_clear[c];
       if (rr < tq) {
         float4* row = reinterpret_cast<float4*>(dq_acc + rr * q_row_elems);
         for (int32_t e = lane; e < q_row_elems / 4; e += 64) row[e] = zero;
@@ -557,6 +583,7 @@ __device__ void row_states(
         for (int32_t e = lane; e < kv_row_elems / 4; e += 64) { rk[e] = zero; rv[e] = zero; }
       }
     }
+    __syncthreads();
   }
 }
 
@@ -638,12 +665,13 @@ __global__ __launch_bounds__(kSchedThreads) void sched_bwd_kernel(
 
 }  // namespace
 
+constexpr int kRowStateBlocks = 128;
 static int row_state_blocks(int32_t tq, int32_t n_kv_rows) {
   int64_t blocks = ((int64_t)tq + n_kv_rows + kSchedThreads / 64 - 1) / (kSchedThreads / 64);
   // Every block stages the whole work list first, so few blocks with several rows per wave.  Measured on the 32K
   // workload (forward / backward scheduling launch): 64 blocks 34 / 81 us, 128 blocks 28 / 50, 256 blocks - / 57,
   // 512 blocks 41 / 58.
-  if (blocks > 128) blocks = 128;
+  if (blocks > kRowStateBlocks) blocks = kRowStateBlocks;
   return blocks < 1 ? 1 : (int)blocks;
 }
 
