@@ -51,6 +51,18 @@ def test_work_list_of_1024_items_through_the_direct_entry_points():
     _say("  " + str({a: b for a, b in res.items() if not a.startswith("_")}))
 
 
+def test_work_list_of_300_unsharded_sequences_in_row_order_through_the_direct_entry_points():
+    """300 unsharded sequences: one item each, query rows and key ranges ascending with the item number (the
+    scheduler finds its sort keys in order and skips the sorts), all rows owned by one unit."""
+    rng = np.random.default_rng(35)
+    lens = rng.integers(1, 200, 300).astype(np.int32)
+    wl = synth.custom_workload(lens, np.ones(300, np.int32), hq=4, hkv=2, head_dim=64, seed=36)
+    q, k, v, do = synth.draw_qkvdo(wl)
+    _say(f"direct work list in row order: 300 sequences, {int(lens.sum())} tokens")
+    res = check_rank(wl, q, k, v, do, 0, backward=True, check_partials=False, label="300 items in row order")
+    _say("  " + str({a: b for a, b in res.items() if not a.startswith("_")}))
+
+
 @pytest.mark.parametrize("family", ["plain", "direct"])
 def test_tensors_as_views_inside_larger_buffers_are_not_overrun(family):
     """Every tensor of the call sits inside a larger allocation: the rows after K and V hold NaN, the rows after each
