@@ -436,7 +436,7 @@ __device__ void build_list(
 // Direct mode of the backward: where does the result of every query row / pool key come from?  State 0: no unit of
 // this launch touches it (the result is zero); 1: it is accumulated in fp32 (several units, atomics) and converted
 // afterwards - its accumulator row is cleared here; 2: one unit owns it and writes the final bf16 row itself.  The
-// states follow the same exclusivity flags the kernels act on.  One wave per row.
+// states follow the same exclusivity flags the kernels act on.  One lane per row, 64-row batches dealt out to the blocks in turn.
 struct RowStateJob {
   uint8_t* q_state;        // NULL: no row states in this launch
   uint8_t* kv_state;       // NULL: query rows only (forward)
