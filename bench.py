@@ -238,6 +238,10 @@ def main():
                     help="leave out the secondary measurements (other workloads, merge at size, degree sweep)")
     ap.add_argument("--secondary-steps", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--operands", choices=["normal", "zero"], default="normal",
+                    help="normal (default): the workload's N(0,1) inputs.  zero: the same launches on all-zero Q, K, V, dO - "
+                         "a diagnostic of how far the chip's clock under matrix load depends on the operand data (the "
+                         "instruction streams are the same); its line says so in `data` and is not a throughput claim")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy after the timed steps: the reference dispatch for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -259,6 +263,8 @@ def main():
     q, k, v, do = synth.draw_qkvdo(wl)
     spans = synth.image_spans(wl.seq_lens, wl.seed) if args.mask == "mixed" else None
     ra = RankAttention(wl.seq_lens, wl.cp_degree, wl.rank, wl.hq, wl.hkv, wl.head_dim, wl.softmax_scale, spans=spans)
+    if args.operands == "zero":
+        q, k, v, do = (np.zeros_like(x) for x in (q, k, v, do))
     ra.set_inputs(q, k, v, do)
     wl_name = wl.name + ("_img576" if spans is not None else "")
     pairs = rank_pairs(ra)
@@ -270,13 +276,15 @@ def main():
     # roofline of the dominant launch: algorithmic flops of one backward step over the AVERAGE duration of the launch
     bwd_mean_ms = kern["bwd_step"]["ms"]["mean"]
     bwd_tflops = 10.0 * pairs * wl.head_dim * wl.hq / (bwd_mean_ms * 1e-3) / 1e12
-    default_line = args.workload == 2 and args.mask == "causal" and args.forward == "direct" and args.backward == "direct"
+    default_line = (args.workload == 2 and args.mask == "causal" and args.forward == "direct" and args.backward == "direct"
+                    and args.operands == "normal")
     out = {
         "metric": "rank-local varlen causal attn TFLOP/s fwd+bwd, % of MFMA bf16 peak",
         "value": value, "unit": "TFLOP/s", "pct_of_mfma_bf16_peak": 100.0 * value / PEAK_BF16_TFLOPS,
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "ms_per_step_median": kern["step"]["ms"]["median"], "ms_per_step_min": kern["step"]["ms"]["min"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic" if args.operands == "normal" else "all-zero operands (clock diagnostic, not a throughput claim)",
         "config": {"workload": wl_name, "mask": args.mask, "forward": args.forward, "backward": args.backward, "n_spans": 0 if spans is None else len(spans), "total_tokens": wl.total_tokens, "n_seqs": int(len(wl.seq_lens)),
                    "rank": wl.rank, "rank_rows": ra.tq, "pairs": pairs, "hq": wl.hq, "hkv": wl.hkv,
                    "head_dim": wl.head_dim, "n_parts": ra.n_parts, "max_cp_degree": int(wl.cp_degree.max()),
