@@ -209,6 +209,17 @@ def secondary(steps, warmup):
             rp = rates(ra, seg_p, pairs, "partial", "direct")
             entry["merge_plain"] = rp["merge"]
             entry["merge_plain"]["note"] = "fcp_lse_merge over every row of the rank: the merge's HBM figure"
+            # the same launches on all-zero operands: what the chip's clock does when the matrix units' inputs do not
+            # toggle (a diagnostic, not a throughput claim: the instruction streams are the same)
+            for t in (ra.q, ra.k, ra.v, ra.d_o):
+                t.zero_()
+            _, seg_z = timed_steps(ra, max(3, steps // 2), 2)
+            rz = rates(ra, seg_z, pairs, "direct", "direct")
+            entry["zero_operands_diagnostic"] = {
+                "note": "same launches, Q = K = V = dO = 0: same shader cycles, higher clock (the chip is power-limited "
+                        "on N(0,1) operands); not a throughput claim",
+                "fwd_step_ms": rz["fwd_step"]["ms"]["median"], "fwd_frac_mfma_peak": rz["fwd_step"]["frac_mfma_peak"],
+                "bwd_step_ms": rz["bwd_step"]["ms"]["median"], "bwd_frac_mfma_peak": rz["bwd_step"]["frac_mfma_peak"]}
         out["workloads"][wl.name] = entry
         del ra
         torch.cuda.empty_cache()
