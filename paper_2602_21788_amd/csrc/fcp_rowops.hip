@@ -22,23 +22,12 @@ __device__ inline float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ inline float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
 constexpr int kMaxParts = 16;   // partial slots held in registers by one merge thread
-constexpr int kRowsPerBlock = 16;
 
-// One thread owns 8 consecutive channels of one (row, head); D/8 threads per (row, head);
-// a 256-thread block covers kRowsPerBlock*16/(D/8)... rows of ONE head so that the LSE reads
-// (head-major) are contiguous.
+// Merge of one (row, head) by the D/8 threads that own it: thread c8 has 8 consecutive channels.
 template <int D>
-__global__ __launch_bounds__(256) void merge_kernel(const float* __restrict__ o_part,
-                                                    const float* __restrict__ lse_part, int n_parts,
-                                                    int tq, int hq, uint32_t* __restrict__ o,
-                                                    float* __restrict__ lse, const uint8_t* __restrict__ q_state) {
-  constexpr int TPR = D / 8;              // threads per (row, head)
-  constexpr int ROWS = 256 / TPR;         // rows per block
-  const int h = blockIdx.y;
-  const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
-  const int c8 = threadIdx.x % TPR;
-  if (row >= tq) return;
-  if (q_state && q_state[row] == 2) return;   // direct mode: the forward kernel wrote this row's O and LSE itself
+__device__ inline void merge_row_head(const float* __restrict__ o_part, const float* __restrict__ lse_part, int n_parts,
+                                      int tq, int hq, uint32_t* __restrict__ o, float* __restrict__ lse, int row, int h,
+                                      int c8) {
   const int64_t lse_stride = (int64_t)hq * tq;
   const int64_t o_stride = (int64_t)tq * hq * D;
   float ls[kMaxParts];
@@ -71,6 +60,52 @@ __global__ __launch_bounds__(256) void merge_kernel(const float* __restrict__ o_
   u32x4 out = {pack_bf16(a0[0], a0[1]), pack_bf16(a0[2], a0[3]), pack_bf16(a1[0], a1[1]), pack_bf16(a1[2], a1[3])};
   *reinterpret_cast<u32x4*>(o + off / 2) = out;
   if (c8 == 0) lse[(int64_t)h * tq + row] = tot > 0.f ? m_safe + __logf(tot) : -INFINITY;
+}
+
+// Every row: a 256-thread block covers 256 / (D/8) consecutive rows of ONE head so that the LSE reads (head-major)
+// are contiguous.
+template <int D>
+__global__ __launch_bounds__(256) void merge_kernel(const float* __restrict__ o_part,
+                                                    const float* __restrict__ lse_part, int n_parts,
+                                                    int tq, int hq, uint32_t* __restrict__ o,
+                                                    float* __restrict__ lse) {
+  constexpr int TPR = D / 8;              // threads per (row, head)
+  constexpr int ROWS = 256 / TPR;         // rows per block
+  const int row = blockIdx.x * ROWS + threadIdx.x / TPR;
+  if (row >= tq) return;
+  merge_row_head<D>(o_part, lse_part, n_parts, tq, hq, o, lse, row, blockIdx.y, threadIdx.x % TPR);
+}
+
+// Direct mode: only the rows that the forward kernel did not finish itself are merged (the finished ones have
+// state 2), and in a packed batch those are few.  A launch with a thread for every (row, head, 8 channels) spends its time starting waves that
+// leave at once (9 us for 16 K rows x 32 heads, 58 us for 128 K rows); here a fixed number of waves walks the units
+// (row, group of 64 / (D/8) heads) - wave w takes units w, w + W, ... - and reads the states of 64 of its units at a
+// time, one per lane, so that a unit with nothing to do costs nothing.
+template <int D>
+__global__ __launch_bounds__(256) void merge_direct_kernel(const float* __restrict__ o_part,
+                                                           const float* __restrict__ lse_part, int n_parts,
+                                                           int tq, int hq, uint32_t* __restrict__ o,
+                                                           float* __restrict__ lse, const uint8_t* __restrict__ q_state) {
+  constexpr int TPR = D / 8;              // threads per (row, head)
+  constexpr int HPW = 64 / TPR;           // heads a wave merges at once
+  const int lane = threadIdx.x & 63;
+  const int upr = (hq + HPW - 1) / HPW;   // units per row
+  const int64_t n_units = (int64_t)tq * upr;
+  const int64_t wstride = (int64_t)gridDim.x * 4;
+  const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  for (int64_t u0 = w; u0 < n_units; u0 += 64 * wstride) {
+    const int64_t mine = u0 + lane * wstride;
+    const int st = mine < n_units ? q_state[mine / upr] : 2;
+    uint64_t todo = __builtin_amdgcn_ballot_w64(st != 2);
+    while (todo) {
+      const int l = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int64_t u = u0 + l * wstride;
+      const int row = (int)(u / upr);
+      const int h = (int)(u % upr) * HPW + lane / TPR;
+      if (h < hq) merge_row_head<D>(o_part, lse_part, n_parts, tq, hq, o, lse, row, h, lane % TPR);
+    }
+  }
 }
 
 template <int D>
@@ -114,7 +149,8 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__
 
 // Direct mode of the backward: the rows whose results were accumulated in fp32 (state 1) are converted, rows that
 // no unit touched (state 0) are zero, rows written directly by their unit (state 2) are left alone.  One wave per
-// row of dQ [tq], then dK [tkv], then dV [tkv].
+// row of dQ [tq], then dK [tkv], then dV [tkv]; wave w takes rows w, w + W, w + 2 W, ... and reads the states of 64 of
+// its rows at a time, one per lane, so that the rows it has nothing to do for cost no trip to memory each.
 __global__ __launch_bounds__(256) void finalize_direct_kernel(
     const uint8_t* __restrict__ q_state, const uint8_t* __restrict__ kv_state, int32_t tq, int32_t tkv,
     int32_t q_row_elems, int32_t kv_row_elems, const float* __restrict__ dq_acc, const float* __restrict__ dk_acc,
@@ -123,28 +159,42 @@ __global__ __launch_bounds__(256) void finalize_direct_kernel(
   const int lane = threadIdx.x & 63;
   const int64_t n_rows = (int64_t)tq + 2 * (int64_t)tkv;
   const int64_t wstride = (int64_t)gridDim.x * 4;
-  for (int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); r < n_rows; r += wstride) {
-    int state, elems;
-    const float* src;
-    uint32_t* dst;
-    if (r < tq) {
-      state = q_state[r]; elems = q_row_elems;
-      src = dq_acc + r * q_row_elems; dst = dq_out + r * (q_row_elems / 2);
-    } else {
-      const bool is_v = r >= (int64_t)tq + tkv;
-      const int64_t kr = r - tq - (is_v ? tkv : 0);
-      state = kv_state[kr]; elems = kv_row_elems;
-      src = (is_v ? dv_acc : dk_acc) + kr * kv_row_elems; dst = (is_v ? dv_out : dk_out) + kr * (kv_row_elems / 2);
-    }
-    if (state == 2) continue;
-    for (int32_t e = lane; e < elems / 8; e += 64) {
-      u32x4 o = {0u, 0u, 0u, 0u};
-      if (state == 1) {
-        const f32x4* s4 = reinterpret_cast<const f32x4*>(src) + 2 * e;
-        const f32x4 x0 = s4[0], x1 = s4[1];
-        o = u32x4{pack_bf16(x0[0], x0[1]), pack_bf16(x0[2], x0[3]), pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+  const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  auto state_of = [&](int64_t r) -> int {
+    if (r >= n_rows) return 2;
+    if (r < tq) return q_state[r];
+    const int64_t kr = r - tq;
+    return kv_state[kr >= tkv ? kr - tkv : kr];
+  };
+  for (int64_t r0 = w; r0 < n_rows; r0 += 64 * wstride) {
+    const int mine = state_of(r0 + lane * wstride);                   // lane l: the wave's l-th row from r0 on
+    uint64_t todo = __builtin_amdgcn_ballot_w64(mine != 2);
+    while (todo) {
+      const int l = __builtin_ctzll(todo);
+      todo &= todo - 1;
+      const int state = __builtin_amdgcn_readlane(mine, l);
+      const int64_t r = r0 + l * wstride;
+      int elems;
+      const float* src;
+      uint32_t* dst;
+      if (r < tq) {
+        elems = q_row_elems;
+        src = dq_acc + r * q_row_elems; dst = dq_out + r * (q_row_elems / 2);
+      } else {
+        const bool is_v = r >= (int64_t)tq + tkv;
+        const int64_t kr = r - tq - (is_v ? tkv : 0);
+        elems = kv_row_elems;
+        src = (is_v ? dv_acc : dk_acc) + kr * kv_row_elems; dst = (is_v ? dv_out : dk_out) + kr * (kv_row_elems / 2);
       }
-      reinterpret_cast<u32x4*>(dst)[e] = o;
+      for (int32_t e = lane; e < elems / 8; e += 64) {
+        u32x4 o = {0u, 0u, 0u, 0u};
+        if (state == 1) {
+          const f32x4* s4 = reinterpret_cast<const f32x4*>(src) + 2 * e;
+          const f32x4 x0 = s4[0], x1 = s4[1];
+          o = u32x4{pack_bf16(x0[0], x0[1]), pack_bf16(x0[2], x0[3]), pack_bf16(x1[0], x1[1]), pack_bf16(x1[2], x1[3])};
+        }
+        reinterpret_cast<u32x4*>(dst)[e] = o;
+      }
     }
   }
 }
@@ -167,12 +217,21 @@ static int lse_merge(const float* o_part, const float* lse_part, int32_t n_parts
   if (!aligned16(o_part) || !aligned16(o)) return fail(FCP_ERR_INVALID_ARG, "fcp_lse_merge: o_part/o must be 16-byte aligned");
   if (tq == 0) return FCP_OK;
   hipStream_t st = (hipStream_t)stream;
-  if (head_dim == 128) {
+  if (q_state) {
+    const int hpw = 64 / (head_dim / 8);
+    int64_t blocks = ((int64_t)tq * ((hq + hpw - 1) / hpw) + 3) / 4;
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    if (head_dim == 128)
+      hipLaunchKernelGGL(fcp::merge_direct_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse, q_state);
+    else
+      hipLaunchKernelGGL(fcp::merge_direct_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse, q_state);
+  } else if (head_dim == 128) {
     dim3 grid((tq + 15) / 16, hq);
-    hipLaunchKernelGGL(fcp::merge_kernel<128>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse, q_state);
+    hipLaunchKernelGGL(fcp::merge_kernel<128>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse);
   } else {
     dim3 grid((tq + 31) / 32, hq);
-    hipLaunchKernelGGL(fcp::merge_kernel<64>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse, q_state);
+    hipLaunchKernelGGL(fcp::merge_kernel<64>, grid, dim3(256), 0, st, o_part, lse_part, n_parts, tq, hq, (uint32_t*)o, lse);
   }
   FCP_HIP_CHECK(hipGetLastError());
   return FCP_OK;
@@ -241,7 +300,7 @@ extern "C" int fcp_grad_finalize_direct(const float* dq_acc, const float* dk_acc
   if (!aligned16(dq_acc) || !aligned16(dk_acc) || !aligned16(dv_acc) || !aligned16(dq_out) || !aligned16(dk_out) || !aligned16(dv_out))
     return fail(FCP_ERR_INVALID_ARG, "fcp_grad_finalize_direct: pointers must be 16-byte aligned");
   int64_t blocks = ((int64_t)tq + 2 * (int64_t)tkv + 3) / 4;
-  if (blocks > 16384) blocks = 16384;
+  if (blocks > 2048) blocks = 2048;     // a wave takes several rows; their states come in one load of 64
   hipLaunchKernelGGL(fcp::finalize_direct_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                      fcp::bwd_q_state(scratch, n_work, tq, tkv, hq), fcp::bwd_kv_state(scratch, n_work, tq, tkv, hq), tq, tkv,
                      hq * head_dim, hkv * head_dim, dq_acc, dk_acc, dv_acc, (uint32_t*)dq_out, (uint32_t*)dk_out,
