@@ -33,7 +33,7 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4 SIMD x 1024 
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per fcp_attn_bwd_step(_direct) launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
 # counters read for a plain 1 GiB copy (profiles/bench_packed32k_hbm_traffic.txt); known for the default workload and path only.
-MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "direct"): 4.58e9}
+MEASURED_BWD_TRAFFIC_BYTES = {("packed32k_lognormal24_h32x8_D128", "direct"): 4.52e9}
 SEGMENTS = ["fwd_step", "merge", "zero", "delta", "bwd_step", "finalize"]
 
 
